@@ -1,0 +1,116 @@
+"""CPU oracle for the three operator chains the tenants run.
+
+TEST INFRASTRUCTURE ONLY.  Built from the single-operator oracles in
+``ops.py``; all arithmetic between two tensors that the GPU graph stores is
+fp64, and the oracle rounds to bf16 exactly on the edges where the GPU graph
+stores a bf16 tensor (marked ``# bf16 edge``).  fp32 edges are not rounded
+(2^-24 relative is far below every tolerance used).
+
+The paper (LithOS) does not define these models; it only runs such models as
+tenants (Sections 6 and 7.1).  The shapes are the benchmark configurations:
+a GEMM+bias+GELU+LayerNorm MLP, a post-LayerNorm encoder layer stack with
+full attention, and a pre-norm grouped-query decoder layer stack decoding one
+token against a key/value cache.
+
+Parameters arrive as dicts of numpy arrays: GEMM weights are bf16 bit
+patterns (uint16) stored [K, N]; vectors (bias, norm scale/shift) are fp32.
+"""
+from __future__ import annotations
+
+import math
+import numpy as np
+
+from . import ops
+
+
+def _bits(x64):
+    return ops.f64_to_bf16(x64)
+
+
+# ------------------------------------------------------------------ MLP ----
+
+def mlp_forward(x_bits, layers, eps: float = 1e-5):
+    """h <- LN(GELU(h @ W + b)) per layer.
+
+    x_bits [B,H] bf16 bits.  GELU output is an fp32 edge, LayerNorm output is
+    a bf16 edge (it feeds the next GEMM) except after the last layer (fp32).
+    Returns fp64 [B,H].
+    """
+    h_bits = np.asarray(x_bits, dtype=np.uint16)
+    out = None
+    for i, L in enumerate(layers):
+        u = ops.gemm(h_bits, L["w"])
+        act = ops.bias_act(u, L["b"].astype(np.float64), gelu=True)      # fp32 edge
+        out = ops.layernorm(act, L["gamma"].astype(np.float64), L["beta"].astype(np.float64), eps)
+        if i + 1 < len(layers):
+            h_bits = _bits(out)                                          # bf16 edge
+    return out
+
+
+# -------------------------------------------------------------- encoder ----
+
+def encoder_forward(x32, layers, batch: int, seq: int, heads: int, eps: float = 1e-5):
+    """Post-LayerNorm encoder stack.
+
+    x32 [batch*seq, H] fp32 hidden states (the residual stream is fp32; GEMM
+    inputs are its bf16 rounding).  Returns fp64 [batch*seq, H].
+    """
+    h = np.asarray(x32, dtype=np.float64)
+    T, H = h.shape
+    assert T == batch * seq and H % heads == 0
+    d = H // heads
+    for L in layers:
+        f64 = lambda name: L[name].astype(np.float64)
+        h_bits = _bits(h)                                                # bf16 edge
+        qkv = ops.bias_act(ops.gemm(h_bits, L["w_qkv"]), f64("b_qkv"), gelu=False)
+        qkv = ops.round_bf16(qkv)                                        # bf16 edge
+        qkv4 = qkv.reshape(batch, seq, 3, heads, d)
+        att = ops.attention(qkv4[:, :, 0], qkv4[:, :, 1], qkv4[:, :, 2], 1.0 / math.sqrt(d))
+        att_bits = _bits(att.reshape(T, H))                              # bf16 edge
+        r1 = ops.bias_act(ops.gemm(att_bits, L["w_o"]), f64("b_o"), gelu=False) + h
+        h1 = ops.layernorm(r1, f64("ln1_g"), f64("ln1_b"), eps)          # fp32 edge
+        f = ops.bias_act(ops.gemm(_bits(h1), L["w_1"]), f64("b_1"), gelu=True)
+        f_bits = _bits(f)                                                # bf16 edge
+        r2 = ops.bias_act(ops.gemm(f_bits, L["w_2"]), f64("b_2"), gelu=False) + h1
+        h = ops.layernorm(r2, f64("ln2_g"), f64("ln2_b"), eps)           # fp32 edge
+    return h
+
+
+# -------------------------------------------------------------- decoder ----
+
+def decoder_decode_step(x32, layers, kcache_bits, vcache_bits, n_q: int, n_kv: int,
+                        pos: int, eps: float = 1e-5, theta: float = 10000.0):
+    """One decode step of a pre-norm grouped-query decoder stack.
+
+    x32 [B,H] fp32 hidden state of the current token (position ``pos``).
+    kcache_bits / vcache_bits: per-layer lists of [B, pos, n_kv, d] bf16 bits
+    holding the ``pos`` cached positions; the current token's key/value are
+    appended, so attention covers pos+1 keys.  Weights: w_qkv [H,(n_q+2 n_kv) d],
+    w_o [n_q d, H], w_gu [H, 2F] (gate columns then up columns), w_d [F,H].
+    Returns fp64 [B,H] (no final norm).
+    """
+    x = np.asarray(x32, dtype=np.float64)
+    B, H = x.shape
+    d = H // n_q
+    positions = np.full((B,), pos, dtype=np.int64)
+    for li, L in enumerate(layers):
+        n1 = _bits(ops.rmsnorm(x, L["rms1"].astype(np.float64), eps))    # bf16 edge
+        qkv = ops.round_bf16(ops.gemm(n1, L["w_qkv"]))                   # bf16 edge
+        q = qkv[:, : n_q * d].reshape(B, n_q, d)
+        k = qkv[:, n_q * d: (n_q + n_kv) * d].reshape(B, n_kv, d)
+        v = qkv[:, (n_q + n_kv) * d:].reshape(B, n_kv, d)
+        q = ops.round_bf16(ops.rope(q, positions, theta))                # bf16 edge
+        k = ops.round_bf16(ops.rope(k, positions, theta))                # bf16 edge (cache slot)
+        kc = ops.bf16_to_f64(kcache_bits[li])                            # [B,pos,n_kv,d]
+        vc = ops.bf16_to_f64(vcache_bits[li])
+        k_all = np.concatenate([kc, k[:, None]], axis=1)
+        v_all = np.concatenate([vc, v[:, None]], axis=1)
+        att = ops.attention(q[:, None], k_all, v_all, 1.0 / math.sqrt(d))  # [B,1,n_q,d]
+        att_bits = _bits(att.reshape(B, n_q * d))                        # bf16 edge
+        x = x + ops.gemm(att_bits, L["w_o"])                             # fp32 edge
+        n2 = _bits(ops.rmsnorm(x, L["rms2"].astype(np.float64), eps))    # bf16 edge
+        gu = ops.round_bf16(ops.gemm(n2, L["w_gu"]))                     # bf16 edge
+        F = gu.shape[1] // 2
+        act = _bits(ops.silu_mul(gu[:, :F], gu[:, F:]))                  # bf16 edge
+        x = x + ops.gemm(act, L["w_d"])                                  # fp32 edge
+    return x
