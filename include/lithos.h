@@ -1,0 +1,290 @@
+/*
+ * liblithos - kernel atomization and CU-partition scheduling on one MI355X.
+ *
+ * C ABI.  Every call returns LITHOS_OK (0) or a negative LITHOS_E* code and
+ * never throws; lithos_last_error() returns a thread-local text for the last
+ * failure on the calling thread.
+ *
+ * Memory: the library never allocates, frees or copies tensor memory.  All
+ * pointers inside lithos_op_t are DEVICE pointers owned by the caller, who
+ * keeps them alive until the operation's completion has been observed.
+ * Pointers in the call signatures themselves (out-parameters, masks, result
+ * arrays) are HOST pointers unless a comment says "device".
+ *
+ * Method: LithOS (arXiv 2504.15465).  Citations below name its sections.
+ */
+#ifndef LITHOS_H
+#define LITHOS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LITHOS_OK       0
+#define LITHOS_EINVAL  -1   /* bad shape, alignment, flag or handle; nothing was launched */
+#define LITHOS_EHIP    -2   /* a HIP call failed; text holds hipGetErrorString */
+#define LITHOS_EMASK   -3   /* empty or out-of-range CU mask */
+#define LITHOS_ESTATE  -4   /* call not valid in the object's current state */
+#define LITHOS_ELIMIT  -5   /* a fixed capacity of the library was exceeded */
+
+#define LITHOS_MASK_WORDS 8          /* 256 CUs = 8 x 32-bit words */
+#define LITHOS_MAX_SWEEP  64         /* right-size sweep points */
+
+typedef struct lithos_ctx lithos_ctx_t;
+typedef struct lithos_partition lithos_partition_t;
+typedef struct lithos_tenant lithos_tenant_t;
+
+typedef struct { uint32_t x, y, z; } lithos_dim3;
+
+/* ---- operators --------------------------------------------------------- */
+
+enum {
+    LITHOS_OP_GEMM      = 1,  /* C = op(A) op(B) [+bias][GELU][+residual], bf16 in, fp32 accumulate */
+    LITHOS_OP_BIAS_ACT  = 2,  /* y = act(x + bias) */
+    LITHOS_OP_LAYERNORM = 3,  /* per-row (x-mean)/sqrt(var+eps)*gamma+beta, biased variance */
+    LITHOS_OP_SOFTMAX   = 4,  /* per-row softmax(scale * s) */
+    LITHOS_OP_ATTN_ENC  = 5,  /* full (unmasked) multi-head attention on a packed qkv tensor */
+    LITHOS_OP_ATTN_DEC  = 6,  /* one query token per sequence against a key/value cache, grouped-query */
+    LITHOS_OP_RMSNORM   = 7,  /* x / sqrt(mean(x^2)+eps) * w */
+    LITHOS_OP_ROPE_KV   = 8,  /* rotary embedding of q and k (rotate-half) + append k,v to the cache */
+    LITHOS_OP_SILU_MUL  = 9,  /* silu(gate) * up on a packed [rows, 2F] tensor */
+    LITHOS_OP_SPIN      = 10  /* test kernel: every block spins a fixed number of clock ticks */
+};
+
+/* flags (meaning depends on the kind, see the table below) */
+#define LITHOS_F_TRANS_A   (1u << 0)   /* A is stored [K,M] */
+#define LITHOS_F_TRANS_B   (1u << 1)   /* B is stored [N,K] */
+#define LITHOS_F_BIAS      (1u << 2)   /* add bias[n] (fp32 vector) */
+#define LITHOS_F_GELU      (1u << 3)   /* erf-form GELU after the bias */
+#define LITHOS_F_RESIDUAL  (1u << 4)   /* add residual[m,n] (fp32) after the activation */
+#define LITHOS_F_OUT_F32   (1u << 5)   /* out[0] is fp32 (default bf16) */
+#define LITHOS_F_IN_F32    (1u << 6)   /* in[0] is fp32 (default bf16) */
+
+/* GEMM tile selectors for lithos_op_t.tile (0 = library chooses) */
+#define LITHOS_TILE_64     64    /* 64x64 output tile */
+#define LITHOS_TILE_128    128   /* 128x128 */
+#define LITHOS_TILE_256    256   /* 256x256 */
+#define LITHOS_TILE_SKINNY 1     /* M <= 32 weight-streaming kernel; needs TRANS_B */
+
+/*
+ * One operator instance.  Unused fields are zero.
+ *
+ * kind        dim[]                              in[] / out[]                         ld[] / fparam[]
+ * GEMM        M,N,K                              A,B,bias(f32),residual(f32) / C      lda,ldb,ldc,ldr
+ * BIAS_ACT    rows,cols                          x,bias(f32) / y
+ * LAYERNORM   rows,H                             x,gamma(f32),beta(f32) / y,[y_bf16]   fparam0=eps
+ * SOFTMAX     rows,n                             s / p                                fparam0=scale
+ * ATTN_ENC    batch,heads,seq,d                  qkv[batch*seq,3*heads*d] / o[batch*seq,heads*d]  fparam0=scale
+ * ATTN_DEC    batch,n_q,n_kv,d,keys,cap          q,kcache,vcache / o                  ld0=q row stride; fparam0=scale
+ *             caches are [batch,cap,n_kv,d] bf16; the first `keys` positions are read
+ * RMSNORM     rows,H                             x(f32),w(f32) / y(bf16)              fparam0=eps
+ * ROPE_KV     rows,n_q,n_kv,d,pos,cap            qkv[rows,(n_q+2n_kv)d] (in place) / kcache,vcache   fparam0=theta
+ * SILU_MUL    rows,F                             gu[rows,2F] / y[rows,F]
+ * SPIN        blocks,ticks                       - / -
+ *
+ * bf16 tensors are row-major with 16-byte aligned rows; K, lda, ldb multiples of 8.
+ * LAYERNORM with OUT_F32 may also write a bf16 copy to out[1] (NULL = none).
+ */
+typedef struct lithos_op {
+    int32_t  kind;
+    uint32_t flags;
+    int32_t  op_id;         /* caller's label, echoed in traces; not interpreted */
+    int32_t  tile;
+    int64_t  dim[8];
+    int64_t  ld[4];
+    float    fparam[4];
+    const void* in[6];      /* device */
+    void*    out[2];        /* device */
+} lithos_op_t;
+
+/* ---- context ----------------------------------------------------------- */
+
+typedef struct lithos_config {
+    double   atom_duration_us;   /* Section 4.4 'Operation': target atom length; default 250 */
+    int32_t  max_outstanding;    /* Section 4.3: atoms a tenant may have in flight; default 2 */
+    int32_t  max_outstanding_hp; /* same limit for LITHOS_CLASS_HP tenants; 0 = use max_outstanding */
+    int32_t  steal;              /* Section 4.3 'TPC Stealing' on/off; default 1 */
+    int32_t  atomize;            /* Section 4.4 on/off; default 1 */
+    int32_t  xcd_remap;          /* logical-block remap that undoes round-robin XCD placement; default 1 */
+    double   ema_alpha;          /* Section 4.7 predictor smoothing; default 0.25 */
+} lithos_config_t;
+
+typedef struct lithos_devinfo {
+    int32_t n_cu;            /* compute units */
+    int32_t n_xcd;           /* accelerator dies */
+    int32_t cu_per_xcd;
+    int32_t wave_size;
+    int32_t lds_bytes_per_cu;
+    int32_t clock_khz;
+    int32_t mask_bits_interleaved; /* CU-mask bit i addresses die i % n_xcd (1) or die i / cu_per_xcd (0); probed at init */
+    char    arch[32];
+} lithos_devinfo_t;
+
+/* cfg may be NULL (defaults).  device is a HIP ordinal. */
+int lithos_init(int device, const lithos_config_t* cfg, lithos_ctx_t** out);
+int lithos_shutdown(lithos_ctx_t* ctx);
+int lithos_device_info(lithos_ctx_t* ctx, lithos_devinfo_t* out);
+const char* lithos_last_error(void);
+
+/* ---- CU partitions (the unit of Section 4.2 'Compute Quotas') ----------- */
+
+#define LITHOS_MASK_STRIPED   0   /* n_cus spread evenly over all XCDs */
+#define LITHOS_MASK_WHOLE_XCD 1   /* n_cus taken XCD by XCD (n_cus multiple of cu_per_xcd) */
+
+/* Fill mask_out[LITHOS_MASK_WORDS] with n_cus CUs, skipping the first
+ * `first` CUs of the same policy's enumeration (so two calls with
+ * first=0,n=64 and first=64,n=192 give disjoint masks). */
+int lithos_make_mask(lithos_ctx_t* ctx, int n_cus, int policy, int first, uint32_t* mask_out);
+
+/* A partition owns one CU-masked HIP queue.  mask_words <= LITHOS_MASK_WORDS. */
+int lithos_create_partition(lithos_ctx_t* ctx, const uint32_t* cu_mask, uint32_t mask_words,
+                            lithos_partition_t** out);
+int lithos_destroy_partition(lithos_partition_t* p);
+int lithos_partition_cus(const lithos_partition_t* p, int* n_cus_out);
+/* the partition's HIP stream, as a hipStream_t (for event timing by the caller) */
+int lithos_partition_stream(const lithos_partition_t* p, void** stream_out);
+
+/* Run `n_wg` probe workgroups on the partition; xcd_out/cu_out[n_wg] receive
+ * the die and the (shader-engine, array, CU) hardware id each one ran on. */
+int lithos_probe_partition(lithos_ctx_t* ctx, const lithos_partition_t* p, uint32_t n_wg,
+                           uint32_t* xcd_out, uint32_t* hwid_out);
+
+/* ---- atomized launch (Section 4.4, Algorithm 1) -------------------------- */
+
+/* Logical grid of an operator and how many of its workgroups fit on one CU. */
+int lithos_op_grid(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3* grid_out,
+                   uint32_t* wg_per_cu_out);
+
+/* Run `op` as ceil(total/atom_blocks) launches, atom i covering logical
+ * blocks [i*atom_blocks, min((i+1)*atom_blocks, total)) of the grid numbered
+ * idx = z*gy*gx + y*gx + x.  atom_blocks == 0 or >= total: one launch.
+ * grid {0,0,0} = use lithos_op_grid's; otherwise it must have the same total.
+ * part NULL = an unmasked queue.  stream (hipStream_t, may be NULL = none):
+ * the first atom waits for work already queued on it and it waits for the
+ * last atom, so the caller's own stream work orders with the launch.
+ * Returns after enqueueing; errors in shape/alignment are reported before
+ * anything is launched. */
+int lithos_launch_atomized(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3 grid,
+                           uint32_t atom_blocks, const lithos_partition_t* part, void* stream);
+
+/* Same, for an explicit block range [lo,hi) only (one atom). */
+int lithos_launch_atom(lithos_ctx_t* ctx, const lithos_op_t* op, uint32_t lo, uint32_t hi,
+                       const lithos_partition_t* part);
+
+/* Wait until everything enqueued on the partition (NULL: the unmasked queue) is done. */
+int lithos_partition_sync(lithos_ctx_t* ctx, const lithos_partition_t* part);
+
+/* Exactly-once instrumentation: while set (non-NULL), every workgroup adds 1
+ * to dev_counters[logical block index] (device pointer, n uint32). */
+int lithos_debug_block_counters(lithos_ctx_t* ctx, uint32_t* dev_counters, uint32_t n);
+
+/* ---- right-sizing (Section 4.5; sweep of Section 7.2's kind) ------------- */
+
+typedef struct lithos_rightsize_result {
+    int32_t n_points;
+    int32_t cus[LITHOS_MAX_SWEEP];
+    double  median_us[LITHOS_MAX_SWEEP];
+    int32_t chosen_cus;          /* smallest CU count within (1+slowdown) of the largest count's latency */
+    double  chosen_us;
+    double  full_us;
+    int32_t occupancy_bound_cus; /* ceil(total blocks / resident blocks per CU), Section 4.5 'Filtering Outliers' */
+    double  model_m, model_b;    /* l = m/t + b through the smallest and largest sweep points */
+    int32_t model_cus;           /* smallest t with l(t) <= (1+slowdown) l(T) under that model */
+} lithos_rightsize_result_t;
+
+/* Time `op` (unatomized) on striped masks of cu_lo, cu_lo+cu_step, ... cu_hi
+ * CUs, `warmup` untimed then `reps` timed launches each (device timestamps). */
+int lithos_rightsize(lithos_ctx_t* ctx, const lithos_op_t* op, int cu_lo, int cu_hi, int cu_step,
+                     int warmup, int reps, double slowdown, lithos_rightsize_result_t* out);
+
+/* ---- tenants and the spatial scheduler (Sections 4.2, 4.3, 4.7) ---------- */
+
+#define LITHOS_CLASS_HP 0
+#define LITHOS_CLASS_BE 1
+
+typedef struct lithos_stats {
+    uint64_t kernels;        /* kernels dispatched */
+    uint64_t atoms;          /* atoms launched */
+    uint64_t stolen_atoms;   /* atoms launched on a mask wider than the tenant's quota */
+    uint64_t predictions;    /* atoms launched with a prediction */
+    uint64_t mispredicts;    /* |predicted - measured| > 50 us (Section 7.4) */
+    double   abs_err_sum_us;
+} lithos_stats_t;
+
+/* quota: the partition whose CUs the tenant is guaranteed.  Quotas of
+ * different tenants must be disjoint.  quota NULL makes a pass-through tenant:
+ * every kernel is launched whole, at submission, on an unmasked queue of the
+ * tenant's own (the unpartitioned co-execution that the scheduler is compared
+ * with). */
+int lithos_tenant_create(lithos_ctx_t* ctx, int cls, const lithos_partition_t* quota,
+                         lithos_tenant_t** out);
+int lithos_tenant_destroy(lithos_tenant_t* t);
+/* Enqueue on the tenant's launch queue and return at once (Section 4.2).
+ * The op descriptor is copied.  ticket_out (may be NULL) identifies the kernel. */
+int lithos_submit(lithos_tenant_t* t, const lithos_op_t* op, uint64_t* ticket_out);
+/* Batch boundary: later kernels restart at ordinal 0 (Section 4.7).  Does not block. */
+int lithos_sync_mark(lithos_tenant_t* t);
+/* Block until every kernel submitted so far has completed; implies lithos_sync_mark. */
+int lithos_sync(lithos_tenant_t* t);
+int lithos_poll(lithos_tenant_t* t, uint64_t ticket, int* done_out);
+int lithos_tenant_stats(lithos_tenant_t* t, lithos_stats_t* out);
+
+/* ---- load generators (native, so that two tenants do not share an interpreter lock) */
+/* These stand in for the paper's clients (Section 7.1: high-priority
+ * applications follow a Poisson load, best-effort ones run in a closed loop). */
+
+typedef struct lithos_driver lithos_driver_t;
+
+/* Open loop, in the calling thread: request r is submitted at arrivals_s[r]
+ * seconds after the call starts (never earlier; later only if the thread is
+ * late), as the ops_per_request operators ops[(r % n_variants)*ops_per_request ...]
+ * followed by a batch boundary.  latency_us_out[r] = completion - scheduled
+ * arrival.  Returns when every request has completed. */
+int lithos_drive_open_loop(lithos_tenant_t* t, const lithos_op_t* ops, int ops_per_request, int n_variants,
+                           const double* arrivals_s, int n_requests, double* latency_us_out);
+
+/* Closed loop on a thread of its own: keeps `depth` iterations (each the
+ * ops_per_iter operators followed by a batch boundary) in flight until stopped. */
+int lithos_drive_closed_loop_start(lithos_tenant_t* t, const lithos_op_t* ops, int ops_per_iter, int depth,
+                                   lithos_driver_t** out);
+/* Stops after the iterations in flight; reports completed iterations and the
+ * wall time between the first submission and the last completion. */
+int lithos_drive_closed_loop_stop(lithos_driver_t* d, uint64_t* iterations_out, double* seconds_out);
+
+/* ---- scheduler policy core, steppable with a caller-supplied clock -------- */
+/* The same decision code the dispatcher threads run, without a device: the
+ * caller plays device and clock.  Used to check the policy on a CPU. */
+
+typedef struct lithos_core lithos_core_t;
+
+typedef struct lithos_core_atom {
+    uint64_t atom_id;
+    int32_t  tenant;
+    uint64_t kernel_id;
+    int32_t  ordinal;
+    uint32_t lo, hi;
+    uint32_t group_mask;     /* bit g = CU group g (cus_per_group CUs each) */
+    int32_t  stolen;
+    int32_t  has_prediction;
+    double   predicted_us;
+} lithos_core_atom_t;
+
+int lithos_core_create(const lithos_config_t* cfg, int n_groups, int cus_per_group, lithos_core_t** out);
+int lithos_core_destroy(lithos_core_t* c);
+int lithos_core_add_tenant(lithos_core_t* c, int cls, uint32_t quota_groups, int* tenant_out);
+int lithos_core_submit(lithos_core_t* c, int tenant, uint32_t total_blocks, uint32_t wg_per_cu,
+                       uint64_t* kernel_id_out);
+int lithos_core_sync_mark(lithos_core_t* c, int tenant);
+/* Next atom the tenant should launch at time now_us; *have_out = 0 if none
+ * (nothing queued, or the outstanding limit is reached). */
+int lithos_core_next_atom(lithos_core_t* c, int tenant, double now_us, lithos_core_atom_t* atom_out,
+                          int* have_out);
+int lithos_core_complete(lithos_core_t* c, uint64_t atom_id, double now_us, double measured_us);
+int lithos_core_stats(lithos_core_t* c, int tenant, lithos_stats_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LITHOS_H */

@@ -21,6 +21,7 @@ Both must visit the same blocks.
 """
 from __future__ import annotations
 
+import math
 from typing import Callable, Iterable, List, Sequence, Tuple
 
 Grid = Tuple[int, int, int]
@@ -116,7 +117,7 @@ def atom_count(predicted_us: float, atom_duration_us: float, total: int) -> int:
     """
     if atom_duration_us <= 0:
         raise ValueError("atom_duration must be positive")
-    n = int(-(-predicted_us // atom_duration_us)) if predicted_us > 0 else 1
+    n = math.ceil(predicted_us / atom_duration_us) if predicted_us > 0 else 1
     return max(1, min(n, total))
 
 

@@ -48,6 +48,7 @@ class SimConfig:
     cus_per_group: int = 8
     atom_duration_us: float = 250.0
     max_outstanding: int = 2
+    max_outstanding_hp: int = 0      # 0: high-priority tenants use max_outstanding too
     steal: bool = True
     atomize: bool = True
     ema_alpha: float = 0.25
@@ -192,7 +193,10 @@ class Simulator:
         return b, upb * b
 
     def _dispatch(self, t: Tenant) -> bool:
-        if t.outstanding >= self.cfg.max_outstanding:
+        limit = self.cfg.max_outstanding
+        if t.hp and self.cfg.max_outstanding_hp > 0:
+            limit = self.cfg.max_outstanding_hp
+        if t.outstanding >= limit:
             return False
         while t.cur is None:
             if not t.queue:

@@ -1,0 +1,377 @@
+// Atom-aware row and elementwise kernels for gfx950: bias+activation,
+// LayerNorm, RMSNorm, softmax, SiLU-gate, rotary embedding + cache append,
+// and a fixed-duration spin kernel for scheduler tests.
+//
+// All are HBM-bound (a few flops per byte): the design rule is coalesced
+// access and wavefront reductions, fp32 arithmetic on bf16 or fp32 data.
+// Each workgroup handles the rows / elements named by its LOGICAL block index
+// (LithOS Section 4.4), so any sub-range of blocks is a valid atom.
+#include "common.hpp"
+#include <math.h>
+
+namespace lithos {
+
+struct RowArgs {
+    const void* x;
+    const float* p0;     // bias / gamma / weight
+    const float* p1;     // beta
+    void* y;
+    void* y2;            // optional bf16 copy
+    int64_t rows, cols;
+    float f0;            // eps / scale / theta
+    uint32_t flags;
+    int64_t aux[4];
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <bool F32>
+__device__ __forceinline__ float load_elem(const void* p, int64_t i)
+{
+    if constexpr (F32) return reinterpret_cast<const float*>(p)[i];
+    else return bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(p)[i]);
+}
+
+template <bool F32>
+__device__ __forceinline__ void store_elem(void* p, int64_t i, float v)
+{
+    if constexpr (F32) reinterpret_cast<float*>(p)[i] = v;
+    else reinterpret_cast<uint16_t*>(p)[i] = f32_to_bf16_bits(v);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// Sum over the TPR threads that share a row (TPR = 64: one wavefront;
+// TPR = 256: the whole workgroup through LDS).  Fixed order: deterministic.
+template <int TPR>
+__device__ __forceinline__ float row_sum(float v, float* red)
+{
+    v = wave_sum(v);
+    if constexpr (TPR == 256) {
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        __syncthreads();
+        v = red[0] + red[1] + red[2] + red[3];
+    }
+    return v;
+}
+
+template <int TPR>
+__device__ __forceinline__ float row_max(float v, float* red)
+{
+    v = wave_max(v);
+    if constexpr (TPR == 256) {
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+        __syncthreads();
+        v = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    }
+    return v;
+}
+
+__device__ __forceinline__ float gelu_erf_f(float u)
+{
+    return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
+}
+
+// ---- y = act(x + bias): 2048 consecutive elements per block ---------------
+template <bool IN32, bool OUT32>
+__global__ __launch_bounds__(256) void bias_act_kernel(RowArgs a, AtomArgs atom)
+{
+    const uint32_t L = atom_logical_block(atom);
+    const int64_t total = a.rows * a.cols;
+    const int64_t base = (int64_t)L * 2048;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int64_t idx = base + threadIdx.x + i * 256;
+        if (idx < total) {
+            float v = load_elem<IN32>(a.x, idx);
+            if (a.flags & LITHOS_F_BIAS) v += a.p0[idx % a.cols];
+            if (a.flags & LITHOS_F_GELU) v = gelu_erf_f(v);
+            store_elem<OUT32>(a.y, idx, v);
+        }
+    }
+}
+
+// ---- y[r, :F] = silu(gu[r, :F]) * gu[r, F:2F] ------------------------------
+__global__ __launch_bounds__(256) void silu_mul_kernel(RowArgs a, AtomArgs atom)
+{
+    const uint32_t L = atom_logical_block(atom);
+    const int64_t F = a.cols, total = a.rows * F;
+    const int64_t base = (int64_t)L * 2048;
+    const uint16_t* gu = reinterpret_cast<const uint16_t*>(a.x);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int64_t idx = base + threadIdx.x + i * 256;
+        if (idx < total) {
+            int64_t r = idx / F, c = idx % F;
+            float g = bf16_bits_to_f32(gu[r * 2 * F + c]);
+            float u = bf16_bits_to_f32(gu[r * 2 * F + F + c]);
+            float v = g / (1.0f + expf(-g)) * u;
+            reinterpret_cast<uint16_t*>(a.y)[idx] = f32_to_bf16_bits(v);
+        }
+    }
+}
+
+// ---- LayerNorm: two passes over the row (mean, then centred variance) ------
+template <bool IN32, bool OUT32, int TPR>
+__global__ __launch_bounds__(256) void layernorm_kernel(RowArgs a, AtomArgs atom)
+{
+    __shared__ float red[4];
+    const uint32_t L = atom_logical_block(atom);
+    constexpr int RPB = 256 / TPR;
+    const int64_t row = (int64_t)L * RPB + threadIdx.x / TPR;
+    const int t = threadIdx.x % TPR;
+    const bool live = row < a.rows;
+    const int64_t H = a.cols, off = row * H;
+    float s = 0.0f;
+    if (live) for (int64_t c = t; c < H; c += TPR) s += load_elem<IN32>(a.x, off + c);
+    const float mean = row_sum<TPR>(s, red) / (float)H;
+    float q = 0.0f;
+    if (live) for (int64_t c = t; c < H; c += TPR) { float d = load_elem<IN32>(a.x, off + c) - mean; q += d * d; }
+    const float var = row_sum<TPR>(q, red) / (float)H;
+    const float rstd = 1.0f / sqrtf(var + a.f0);
+    if (live) for (int64_t c = t; c < H; c += TPR) {
+        float v = (load_elem<IN32>(a.x, off + c) - mean) * rstd * a.p0[c] + a.p1[c];
+        store_elem<OUT32>(a.y, off + c, v);
+        if (OUT32 && a.y2) reinterpret_cast<uint16_t*>(a.y2)[off + c] = f32_to_bf16_bits(v);
+    }
+}
+
+// ---- RMSNorm ----------------------------------------------------------------
+template <bool IN32, int TPR>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(RowArgs a, AtomArgs atom)
+{
+    __shared__ float red[4];
+    const uint32_t L = atom_logical_block(atom);
+    constexpr int RPB = 256 / TPR;
+    const int64_t row = (int64_t)L * RPB + threadIdx.x / TPR;
+    const int t = threadIdx.x % TPR;
+    const bool live = row < a.rows;
+    const int64_t H = a.cols, off = row * H;
+    float s = 0.0f;
+    if (live) for (int64_t c = t; c < H; c += TPR) { float v = load_elem<IN32>(a.x, off + c); s += v * v; }
+    const float ms = row_sum<TPR>(s, red) / (float)H;
+    const float rinv = 1.0f / sqrtf(ms + a.f0);
+    if (live) for (int64_t c = t; c < H; c += TPR)
+        reinterpret_cast<uint16_t*>(a.y)[off + c] = f32_to_bf16_bits(load_elem<IN32>(a.x, off + c) * rinv * a.p0[c]);
+}
+
+// ---- softmax(scale * s) -----------------------------------------------------
+template <bool IN32, bool OUT32, int TPR>
+__global__ __launch_bounds__(256) void softmax_kernel(RowArgs a, AtomArgs atom)
+{
+    __shared__ float red[4];
+    const uint32_t L = atom_logical_block(atom);
+    constexpr int RPB = 256 / TPR;
+    const int64_t row = (int64_t)L * RPB + threadIdx.x / TPR;
+    const int t = threadIdx.x % TPR;
+    const bool live = row < a.rows;
+    const int64_t n = a.cols, off = row * n;
+    float mx = -INFINITY;
+    if (live) for (int64_t c = t; c < n; c += TPR) mx = fmaxf(mx, load_elem<IN32>(a.x, off + c) * a.f0);
+    mx = row_max<TPR>(mx, red);
+    float s = 0.0f;
+    if (live) for (int64_t c = t; c < n; c += TPR) s += expf(load_elem<IN32>(a.x, off + c) * a.f0 - mx);
+    const float den = row_sum<TPR>(s, red);
+    if (live) for (int64_t c = t; c < n; c += TPR)
+        store_elem<OUT32>(a.y, off + c, expf(load_elem<IN32>(a.x, off + c) * a.f0 - mx) / den);
+}
+
+// ---- rotary embedding of q and k heads in place + k,v appended to the cache --
+// One wavefront per (row, head slot); slots 0..n_q-1 are query heads,
+// n_q..n_q+n_kv-1 key heads, the rest value heads (copied to the cache only).
+// aux = {n_q, n_kv, pos, cap}; cols = d.
+__global__ __launch_bounds__(256) void rope_kv_kernel(RowArgs a, AtomArgs atom)
+{
+    const uint32_t L = atom_logical_block(atom);
+    const int64_t n_q = a.aux[0], n_kv = a.aux[1], pos = a.aux[2], cap = a.aux[3], d = a.cols;
+    const int64_t slots = n_q + 2 * n_kv;
+    const int64_t unit = (int64_t)L * 4 + (threadIdx.x >> 6);
+    if (unit >= a.rows * slots) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t row = unit / slots, slot = unit % slots;
+    uint16_t* head = reinterpret_cast<uint16_t*>(const_cast<void*>(a.x)) + row * slots * d + slot * d;
+    uint16_t* kc = reinterpret_cast<uint16_t*>(a.y);
+    uint16_t* vc = reinterpret_cast<uint16_t*>(a.y2);
+    const int64_t half = d / 2;
+    if (slot < n_q + n_kv) {
+        uint16_t* dst = nullptr;
+        if (slot >= n_q) dst = kc + ((row * cap + pos) * n_kv + (slot - n_q)) * d;
+        for (int64_t e = lane; e < half; e += 64) {
+            float inv = powf(a.f0, -2.0f * (float)e / (float)d);
+            float sn, cs;
+            sincosf((float)pos * inv, &sn, &cs);
+            float x0 = bf16_bits_to_f32(head[e]), x1 = bf16_bits_to_f32(head[e + half]);
+            uint16_t y0 = f32_to_bf16_bits(x0 * cs - x1 * sn);
+            uint16_t y1 = f32_to_bf16_bits(x1 * cs + x0 * sn);
+            head[e] = y0; head[e + half] = y1;
+            if (dst) { dst[e] = y0; dst[e + half] = y1; }
+        }
+    } else {
+        uint16_t* dst = vc + ((row * cap + pos) * n_kv + (slot - n_q - n_kv)) * d;
+        for (int64_t e = lane; e < d; e += 64) dst[e] = head[e];
+    }
+}
+
+// ---- spin: every block waits `ticks` of the constant 100 MHz counter -------
+__global__ __launch_bounds__(64) void spin_kernel(uint64_t ticks, AtomArgs atom)
+{
+    (void)atom_logical_block(atom);
+    const uint64_t t0 = wall_clock64();
+    while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(8);
+}
+
+// ---- host side ----------------------------------------------------------------
+
+static RowArgs make_args(const lithos_op_t& op)
+{
+    RowArgs a{};
+    a.x = op.in[0];
+    a.p0 = (const float*)op.in[1];
+    a.p1 = (const float*)op.in[2];
+    a.y = op.out[0];
+    a.y2 = op.out[1];
+    a.rows = op.dim[0];
+    a.cols = op.dim[1];
+    a.f0 = op.fparam[0];
+    a.flags = op.flags;
+    return a;
+}
+
+static int tpr_for(int64_t cols) { return cols <= 1024 ? 64 : 256; }
+
+int rowops_plan(const lithos_op_t& op, OpPlan* plan)
+{
+    const int64_t rows = op.dim[0], cols = op.dim[1];
+    if (rows <= 0 || cols <= 0 || rows > (1ll << 31) || cols > (1ll << 24))
+        return fail(LITHOS_EINVAL, "row op %d: rows and cols must be positive (got %lld, %lld)", op.kind, (long long)rows, (long long)cols);
+    if (!op.in[0] && op.kind != LITHOS_OP_SPIN) return fail(LITHOS_EINVAL, "row op %d: null input", op.kind);
+    plan->threads = 256;
+    plan->variant = 0;
+    plan->wg_per_cu = 8;
+    uint64_t blocks = 0;
+    switch (op.kind) {
+    case LITHOS_OP_BIAS_ACT:
+        if (!op.out[0]) return fail(LITHOS_EINVAL, "bias_act: null output");
+        if ((op.flags & LITHOS_F_BIAS) && !op.in[1]) return fail(LITHOS_EINVAL, "bias_act: BIAS set but in[1] is null");
+        blocks = ((uint64_t)rows * cols + 2047) / 2048;
+        break;
+    case LITHOS_OP_SILU_MUL:
+        if (!op.out[0]) return fail(LITHOS_EINVAL, "silu_mul: null output");
+        blocks = ((uint64_t)rows * cols + 2047) / 2048;
+        break;
+    case LITHOS_OP_LAYERNORM:
+        if (!op.in[1] || !op.in[2] || !op.out[0]) return fail(LITHOS_EINVAL, "layernorm: null gamma, beta or output");
+        if (!(op.flags & LITHOS_F_OUT_F32) && op.out[1]) return fail(LITHOS_EINVAL, "layernorm: a bf16 copy needs OUT_F32");
+        blocks = (rows + (256 / tpr_for(cols)) - 1) / (256 / tpr_for(cols));
+        break;
+    case LITHOS_OP_RMSNORM:
+        if (!op.in[1] || !op.out[0]) return fail(LITHOS_EINVAL, "rmsnorm: null weight or output");
+        blocks = (rows + (256 / tpr_for(cols)) - 1) / (256 / tpr_for(cols));
+        break;
+    case LITHOS_OP_SOFTMAX:
+        if (!op.out[0]) return fail(LITHOS_EINVAL, "softmax: null output");
+        blocks = (rows + (256 / tpr_for(cols)) - 1) / (256 / tpr_for(cols));
+        break;
+    case LITHOS_OP_ROPE_KV: {
+        // dim = rows, n_q, n_kv, d, pos, cap
+        const int64_t n_q = op.dim[1], n_kv = op.dim[2], d = op.dim[3], pos = op.dim[4], cap = op.dim[5];
+        if (n_q <= 0 || n_kv <= 0 || d <= 0 || (d & 1) || pos < 0 || pos >= cap)
+            return fail(LITHOS_EINVAL, "rope_kv: need n_q,n_kv,d > 0, d even, 0 <= pos < cap");
+        if (!op.out[0] || !op.out[1]) return fail(LITHOS_EINVAL, "rope_kv: null cache pointer");
+        blocks = ((uint64_t)rows * (n_q + 2 * n_kv) + 3) / 4;
+        break;
+    }
+    case LITHOS_OP_SPIN:
+        if (op.dim[1] < 0 || op.dim[1] > 100000000) return fail(LITHOS_EINVAL, "spin: ticks must be in [0, 1e8] (1 s)");
+        blocks = rows;
+        plan->threads = 64;
+        plan->wg_per_cu = 1;
+        break;
+    default:
+        return fail(LITHOS_EINVAL, "unknown row op kind %d", op.kind);
+    }
+    if (blocks == 0 || blocks > 0x7fffffffull) return fail(LITHOS_EINVAL, "row op %d: grid out of range", op.kind);
+    plan->grid = {(uint32_t)blocks, 1, 1};
+    plan->total = (uint32_t)blocks;
+    return LITHOS_OK;
+}
+
+int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, hipStream_t s)
+{
+    RowArgs a = make_args(op);
+    const bool in32 = op.flags & LITHOS_F_IN_F32, out32 = op.flags & LITHOS_F_OUT_F32;
+    const dim3 grid(atom.n), block(plan.threads);
+    hipError_t e = hipSuccess;
+#define L2(K, A, B) e = launch_kernel(K<A, B>, grid, block, s, a, atom)
+#define L3(K, A, B, C) e = launch_kernel(K<A, B, C>, grid, block, s, a, atom)
+    switch (op.kind) {
+    case LITHOS_OP_BIAS_ACT:
+        if (in32) { if (out32) L2(bias_act_kernel, true, true); else L2(bias_act_kernel, true, false); }
+        else      { if (out32) L2(bias_act_kernel, false, true); else L2(bias_act_kernel, false, false); }
+        break;
+    case LITHOS_OP_SILU_MUL:
+        e = launch_kernel(silu_mul_kernel, grid, block, s, a, atom);
+        break;
+    case LITHOS_OP_LAYERNORM:
+        if (tpr_for(a.cols) == 64) {
+            if (in32) { if (out32) L3(layernorm_kernel, true, true, 64); else L3(layernorm_kernel, true, false, 64); }
+            else      { if (out32) L3(layernorm_kernel, false, true, 64); else L3(layernorm_kernel, false, false, 64); }
+        } else {
+            if (in32) { if (out32) L3(layernorm_kernel, true, true, 256); else L3(layernorm_kernel, true, false, 256); }
+            else      { if (out32) L3(layernorm_kernel, false, true, 256); else L3(layernorm_kernel, false, false, 256); }
+        }
+        break;
+    case LITHOS_OP_RMSNORM:
+        if (tpr_for(a.cols) == 64) { if (in32) L2(rmsnorm_kernel, true, 64); else L2(rmsnorm_kernel, false, 64); }
+        else                       { if (in32) L2(rmsnorm_kernel, true, 256); else L2(rmsnorm_kernel, false, 256); }
+        break;
+    case LITHOS_OP_SOFTMAX:
+        if (tpr_for(a.cols) == 64) {
+            if (in32) { if (out32) L3(softmax_kernel, true, true, 64); else L3(softmax_kernel, true, false, 64); }
+            else      { if (out32) L3(softmax_kernel, false, true, 64); else L3(softmax_kernel, false, false, 64); }
+        } else {
+            if (in32) { if (out32) L3(softmax_kernel, true, true, 256); else L3(softmax_kernel, true, false, 256); }
+            else      { if (out32) L3(softmax_kernel, false, true, 256); else L3(softmax_kernel, false, false, 256); }
+        }
+        break;
+    case LITHOS_OP_ROPE_KV:
+        a.cols = op.dim[3];
+        a.aux[0] = op.dim[1]; a.aux[1] = op.dim[2]; a.aux[2] = op.dim[4]; a.aux[3] = op.dim[5];
+        a.p0 = nullptr; a.p1 = nullptr;
+        e = launch_kernel(rope_kv_kernel, grid, block, s, a, atom);
+        break;
+    case LITHOS_OP_SPIN:
+        e = launch_kernel(spin_kernel, grid, block, s, (uint64_t)op.dim[1], atom);
+        break;
+    default:
+        return fail(LITHOS_EINVAL, "unknown row op kind %d", op.kind);
+    }
+#undef L2
+#undef L3
+    LITHOS_HIP(e);
+    return LITHOS_OK;
+}
+
+} // namespace lithos

@@ -1,0 +1,191 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its scheduler policy core takes the same decisions as the
+oracle's scheduler model on the same scenario (no compute calls, no GPU)."""
+import os
+import random
+import re
+
+import pytest
+
+from oracle.sched_sim import Kernel, SimConfig, Simulator
+from paper_2504_15465_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lithos.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lithos_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _declared_symbols()
+    assert len(names) >= 30
+    for n in names:
+        assert hasattr(lib, n), "liblithos.so does not export %s" % n
+    assert sorted(B.EXPORTS) == names, "binding and header disagree"
+
+
+def test_binding_struct_sizes_match_the_header_layout():
+    import ctypes as C
+    assert C.sizeof(B.Op) == 4 * 4 + 8 * 8 + 4 * 8 + 4 * 4 + 6 * 8 + 2 * 8
+    assert C.sizeof(B.Dim3) == 12
+    assert C.sizeof(B.CoreAtom) == 56
+    assert C.sizeof(B.Stats) == 48
+
+
+def test_core_rejects_bad_arguments():
+    with pytest.raises(B.LithosError) as e:
+        B.lithos_core_create(None, 0, 8)
+    assert e.value.code == B.EINVAL
+    c = B.lithos_core_create(None, 32, 8)
+    t0 = B.lithos_core_add_tenant(c, B.CLASS_HP, 0xFF)
+    with pytest.raises(B.LithosError) as e:
+        B.lithos_core_add_tenant(c, B.CLASS_BE, 0x80)          # overlaps tenant 0
+    assert e.value.code == B.EMASK
+    with pytest.raises(B.LithosError):
+        B.lithos_core_add_tenant(c, B.CLASS_BE, 0)             # empty quota
+    with pytest.raises(B.LithosError):
+        B.lithos_core_submit(c, 5, 10)                         # unknown tenant
+    with pytest.raises(B.LithosError):
+        B.lithos_core_submit(c, t0, 0)                         # empty kernel
+    with pytest.raises(B.LithosError) as e:
+        B.lithos_core_complete(c, 12345, 0.0, 1.0)             # not in flight
+    assert e.value.code == B.ESTATE
+    assert B.lithos_core_next_atom(c, t0, 0.0) is None
+    B.lithos_core_destroy(c)
+
+
+# ---- lock-step comparison with the oracle's scheduler model -------------------
+
+HP_Q = frozenset(range(0, 8))
+BE_Q = frozenset(range(8, 32))
+
+
+def _lat(op, cus, blocks):
+    per_block = {"be": 62.5, "hp_a": 20.0, "hp_b": 24.0}[op]
+    return 2.0 + per_block * blocks / cus
+
+
+def _bits(groups):
+    m = 0
+    for g in groups:
+        m |= 1 << g
+    return m
+
+
+class CoreHarness:
+    """Plays clock and device for the C policy core exactly as the oracle's
+    simulator plays them for its own policy (exclusive CU groups, stream order)."""
+
+    def __init__(self, cfg: B.Config, ops_by_kernel):
+        self.c = B.lithos_core_create(cfg, 32, 8)
+        self.hp = B.lithos_core_add_tenant(self.c, B.CLASS_HP, _bits(HP_Q))
+        self.be = B.lithos_core_add_tenant(self.c, B.CLASS_BE, _bits(BE_Q))
+        self.group_free = [0.0] * 32
+        self.last_end = {self.hp: 0.0, self.be: 0.0}
+        self.events = []
+        self.seq = 0
+        self.trace = []
+        self.op_of = ops_by_kernel
+
+    def push(self, time, kind, payload):
+        import heapq
+        heapq.heappush(self.events, (time, self.seq, kind, payload))
+        self.seq += 1
+
+    def dispatch_all(self, now):
+        progressed = True
+        while progressed:
+            progressed = False
+            for t in (self.hp, self.be):
+                a = B.lithos_core_next_atom(self.c, t, now)
+                if a is None:
+                    continue
+                progressed = True
+                groups = [g for g in range(32) if a.group_mask >> g & 1]
+                cus = 8 * len(groups)
+                start = max(now, self.last_end[t], max(self.group_free[g] for g in groups))
+                dur = _lat(self.op_of[a.kernel_id], cus, a.hi - a.lo)
+                end = start + dur
+                self.last_end[t] = end
+                for g in groups:
+                    self.group_free[g] = end
+                self.trace.append((t, a.ordinal, a.lo, a.hi, a.group_mask, bool(a.stolen),
+                                   a.predicted_us if a.has_prediction else None, start, end))
+                self.push(end, "complete", (a.atom_id, dur))
+
+    def run(self):
+        import heapq
+        while self.events:
+            time, _, kind, payload = heapq.heappop(self.events)
+            if kind == "submit":
+                t, total, op = payload
+                kid = B.lithos_core_submit(self.c, t, total, 1)
+                self.op_of[kid] = op
+            elif kind == "sync":
+                B.lithos_core_sync_mark(self.c, payload)
+            else:
+                atom_id, dur = payload
+                B.lithos_core_complete(self.c, atom_id, time, dur)
+            self.dispatch_all(time)
+
+
+@pytest.mark.parametrize("atomize,steal,atom_us,max_out,max_out_hp", [
+    (True, True, 100.0, 2, 0), (False, True, 100.0, 2, 0), (True, False, 100.0, 2, 0),
+    (True, True, 40.0, 3, 8), (True, True, 400.0, 1, 4)])
+def test_policy_core_matches_oracle_model_step_by_step(atomize, steal, atom_us, max_out, max_out_hp):
+    rnd = random.Random(42)
+    hp_times = sorted(rnd.uniform(100, 30000) for _ in range(40))
+    scenario = []                      # (time, kind, tenant, total, op)
+    for i in range(50):
+        scenario.append((0.0, "submit", "be", 1024, "be"))
+        scenario.append((0.0, "sync", "be", 0, ""))
+    for t in hp_times:
+        scenario.append((t, "submit", "hp", 64, "hp_a"))
+        scenario.append((t, "submit", "hp", 48, "hp_b"))
+        scenario.append((t, "sync", "hp", 0, ""))
+
+    # oracle model
+    sim = Simulator(SimConfig(atom_duration_us=atom_us, max_outstanding=max_out, max_outstanding_hp=max_out_hp,
+                              steal=steal, atomize=atomize), _lat)
+    hp = sim.add_tenant(HP_Q, hp=True)
+    be = sim.add_tenant(BE_Q, hp=False)
+    for time, kind, who, total, op in scenario:
+        tid = hp if who == "hp" else be
+        if kind == "submit":
+            sim.submit_at(time, tid, Kernel(op, total, 1))
+        else:
+            sim.sync_at(time, tid)
+    sim.run()
+    want = [(a.tenant, a.ordinal, a.lo, a.hi, _bits(a.mask), a.stolen, a.predicted_us, a.t_start, a.t_end)
+            for a in sim.trace]
+
+    # C core under the same clock and device
+    cfg = B.Config.default(atom_duration_us=atom_us, max_outstanding=max_out, max_outstanding_hp=max_out_hp,
+                           steal=int(steal), atomize=int(atomize))
+    h = CoreHarness(cfg, {})
+    for time, kind, who, total, op in scenario:
+        tid = h.hp if who == "hp" else h.be
+        if kind == "submit":
+            h.push(time, "submit", (tid, total, op))
+        else:
+            h.push(time, "sync", tid)
+    h.run()
+
+    assert len(h.trace) == len(want)
+    for got, exp in zip(h.trace, want):
+        assert got[:6] == exp[:6], (got, exp)
+        if exp[6] is None:
+            assert got[6] is None
+        else:
+            assert abs(got[6] - exp[6]) < 1e-9
+        assert abs(got[7] - exp[7]) < 1e-9 and abs(got[8] - exp[8]) < 1e-9
+    s_hp, s_be = B.lithos_core_stats(h.c, h.hp), B.lithos_core_stats(h.c, h.be)
+    assert s_hp.atoms + s_be.atoms == sim.stats["atoms"]
+    assert s_hp.stolen_atoms + s_be.stolen_atoms == sim.stats["steals"]
+    assert s_hp.mispredicts + s_be.mispredicts == sim.stats["mispredicts"]
+    assert s_hp.predictions + s_be.predictions == sim.stats["predictions"]
+    B.lithos_core_destroy(h.c)

@@ -1,0 +1,185 @@
+"""GPU parity of the atomized bf16 GEMM against the fp64 oracle (C-ABI calls)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import atoms as A
+from oracle import ops as O
+from paper_2504_15465_amd import binding as B
+from paper_2504_15465_amd import inputs
+from gpu_util import bits_equal, bf16_close, counters, ctx, dev_bits, nan_like, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+FRO_TOL = 1e-4      # per-GEMM bar: relative Frobenius error vs fp64 accumulation on the same bf16 inputs
+
+
+def run_gemm(a_bits, b_bits, m, n, k, ta=False, tb=False, tile=0, atom_blocks=0, part=None, out_dtype=torch.float32,
+             bias=None, gelu=False, residual=None, count=False):
+    c = nan_like((m, n), out_dtype)
+    a, b = dev_bits(a_bits), dev_bits(b_bits)
+    op = B.gemm_op(a, b, c, m, n, k, ta=ta, tb=tb, tile=tile, bias=bias, gelu=gelu, residual=residual)
+    grid, _ = B.lithos_op_grid(ctx(), op)
+    cnt = None
+    if count:
+        cnt = counters(grid[0] * grid[1] * grid[2])
+        B.lithos_debug_block_counters(ctx(), cnt)
+    try:
+        B.lithos_launch_atomized(ctx(), op, (0, 0, 0), atom_blocks, part, None)
+        B.lithos_partition_sync(ctx(), part)
+    finally:
+        B.lithos_debug_block_counters(ctx(), None)
+    return c, grid, cnt
+
+
+def test_config1_single_atomized_gemm():
+    """512^3, U[-1,1] seed 0, 64x64 tiles = 64 blocks, 8 atoms of 8 on a 32-CU mask."""
+    m = n = k = 512
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=0)
+    part = B.lithos_create_partition(ctx(), B.lithos_make_mask(ctx(), 32))
+    try:
+        c_atom, grid, cnt = run_gemm(a_bits, b_bits, m, n, k, tile=64, atom_blocks=8, part=part, count=True)
+        assert grid == (8, 8, 1)
+        assert len(A.decompose(grid, 8)) == 8
+        assert cnt.cpu().tolist() == [1] * 64                     # every block exactly once
+        c_full, _, _ = run_gemm(a_bits, b_bits, m, n, k, tile=64, atom_blocks=0, part=part)
+        assert bits_equal(c_atom, c_full)                         # bit-exact vs the unatomized launch
+        c_nomask, _, _ = run_gemm(a_bits, b_bits, m, n, k, tile=64, atom_blocks=0, part=None)
+        assert bits_equal(c_atom, c_nomask)
+        ref = O.gemm(a_bits, b_bits)
+        assert rel_fro(c_atom, ref) <= FRO_TOL
+    finally:
+        B.lithos_destroy_partition(part)
+
+
+@pytest.mark.parametrize("tile", [64, 128, 256])
+@pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, False), (True, True)])
+def test_tiles_layouts_ragged_shapes(tile, ta, tb):
+    # several tiles in each direction plus a ragged tail in M, N and K
+    m, n, k = (200, 328, 136) if tile == 64 else (392, 520, 200) if tile == 128 else (520, 776, 264)
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=tile + 2 * ta + tb, ta=ta, tb=tb)
+    ref = O.gemm(a_bits, b_bits, ta=ta, tb=tb)
+    c_full, grid, _ = run_gemm(a_bits, b_bits, m, n, k, ta, tb, tile)
+    assert not torch.isnan(c_full).any()
+    assert rel_fro(c_full, ref) <= FRO_TOL
+    total = grid[0] * grid[1]
+    for atom_blocks in (1, 3, total - 1):
+        c_atom, _, cnt = run_gemm(a_bits, b_bits, m, n, k, ta, tb, tile, atom_blocks=atom_blocks, count=True)
+        assert cnt.cpu().tolist() == [1] * total
+        assert bits_equal(c_atom, c_full)
+
+
+def test_exactly_representable_data_matches_oracle_bit_for_bit():
+    rng = np.random.default_rng(1)
+    vals = np.array([1, -1, .5, -.5, 2, -2], np.float32)
+    m, n, k = 256, 192, 512
+    a = vals[rng.integers(0, 6, (m, k))]
+    b = vals[rng.integers(0, 6, (k, n))]
+    a_bits, b_bits = inputs.to_bf16_bits(a), inputs.to_bf16_bits(b)
+    ref = O.gemm(a_bits, b_bits)
+    for tile in (64, 128, 256):
+        c, _, _ = run_gemm(a_bits, b_bits, m, n, k, tile=tile)
+        assert np.array_equal(c.cpu().numpy().astype(np.float64), ref)
+    ones_a = inputs.to_bf16_bits(np.ones((64, 1024), np.float32))
+    ones_b = inputs.to_bf16_bits(np.ones((1024, 64), np.float32))
+    c, _, _ = run_gemm(ones_a, ones_b, 64, 64, 1024, tile=64)
+    assert bool((c == 1024.0).all())
+
+
+@pytest.mark.parametrize("tile,tb", [(64, False), (128, True), (B.TILE_SKINNY, True)])
+def test_fused_epilogue_bias_gelu_residual(tile, tb):
+    m, n, k = (24, 200, 264) if tile == B.TILE_SKINNY else (136, 200, 264)
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=9, tb=tb)
+    bias = inputs.normal_f32((n,), 10, 0.5)
+    resid = inputs.normal_f32((m, n), 11, 1.0)
+    acc = O.gemm(a_bits, b_bits, tb=tb)
+    ref = O.bias_act(acc, bias.astype(np.float64), gelu=True) + resid.astype(np.float64)
+    bias_d, resid_d = torch.from_numpy(bias).cuda(), torch.from_numpy(resid).cuda()
+    c32, _, _ = run_gemm(a_bits, b_bits, m, n, k, tb=tb, tile=tile, bias=bias_d, gelu=True, residual=resid_d)
+    assert np.abs(c32.cpu().numpy().astype(np.float64) - ref).max() <= 2e-4 * max(1.0, np.abs(ref).max())
+    c16, _, _ = run_gemm(a_bits, b_bits, m, n, k, tb=tb, tile=tile, bias=bias_d, gelu=True, residual=resid_d,
+                         out_dtype=torch.bfloat16)
+    bf16_close(c16, ref)
+    c16a, _, _ = run_gemm(a_bits, b_bits, m, n, k, tb=tb, tile=tile, bias=bias_d, gelu=True, residual=resid_d,
+                          out_dtype=torch.bfloat16, atom_blocks=2)
+    assert bits_equal(c16, c16a)
+
+
+@pytest.mark.parametrize("m", [1, 8, 13, 16, 32])
+@pytest.mark.parametrize("n,k", [(4096, 4096), (1000, 520)])
+def test_skinny_weight_streaming_gemm(m, n, k):
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=m, tb=True, dist="normal")
+    ref = O.gemm(a_bits, b_bits, tb=True)
+    c, grid, cnt = run_gemm(a_bits, b_bits, m, n, k, tb=True, tile=B.TILE_SKINNY, count=True)
+    assert grid == ((n + 15) // 16, 1, 1)
+    assert cnt.cpu().tolist() == [1] * grid[0]
+    assert not torch.isnan(c).any()
+    assert rel_fro(c, ref) <= FRO_TOL
+    c_atom, _, _ = run_gemm(a_bits, b_bits, m, n, k, tb=True, tile=B.TILE_SKINNY, atom_blocks=7)
+    assert bits_equal(c, c_atom)
+    # auto selection picks the same kernel for small M with a [N,K] weight
+    c_auto, grid_auto, _ = run_gemm(a_bits, b_bits, m, n, k, tb=True, tile=0)
+    assert grid_auto == grid and bits_equal(c, c_auto)
+
+
+def test_full_size_8192_cubed_sampled_rows():
+    """The benchmark's best-effort GEMM at full size, 256x256 tiles, in the
+    launch shape bench.py times (unatomized and cut in atoms of 256 blocks);
+    64 sampled full rows of C are checked against the oracle."""
+    m = n = k = 8192
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=4)
+    a, b = dev_bits(a_bits), dev_bits(b_bits)
+    c_full = nan_like((m, n), torch.float32)
+    c_atom = nan_like((m, n), torch.float32)
+    op_full = B.gemm_op(a, b, c_full, m, n, k, tile=256)
+    op_atom = B.gemm_op(a, b, c_atom, m, n, k, tile=256)
+    grid, _ = B.lithos_op_grid(ctx(), op_full)
+    assert grid == (32, 32, 1)
+    cnt = counters(1024)
+    B.lithos_launch_atomized(ctx(), op_full, (0, 0, 0), 0, None, None)
+    B.lithos_debug_block_counters(ctx(), cnt)
+    try:
+        B.lithos_launch_atomized(ctx(), op_atom, (0, 0, 0), 256, None, None)
+        B.lithos_partition_sync(ctx(), None)
+    finally:
+        B.lithos_debug_block_counters(ctx(), None)
+    assert cnt.cpu().tolist() == [1] * 1024
+    assert bits_equal(c_full, c_atom)
+    rows = np.sort(np.random.default_rng(0).choice(m, 64, replace=False))
+    ref = O.gemm(a_bits[rows], b_bits)
+    assert rel_fro(c_full[torch.from_numpy(rows).cuda()], ref) <= FRO_TOL
+
+
+def test_bf16_output_full_size_edge():
+    m, n, k = 2048, 2048, 2048
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=5, dist="normal")
+    c, _, _ = run_gemm(a_bits, b_bits, m, n, k, tile=256, out_dtype=torch.bfloat16)
+    bf16_close(c, O.gemm(a_bits, b_bits))
+
+
+def test_bad_arguments_are_refused_before_launch():
+    a = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros((64, 64), dtype=torch.float32, device="cuda")
+    cases = [
+        B.gemm_op(a, a, c, 64, 64, 60),                      # K not a multiple of 8
+        B.gemm_op(a, a, c, 64, 64, 64, lda=60),              # lda not a multiple of 8
+        B.gemm_op(a, a, c, 64, 60, 64),                      # N % 8 with non-transposed B
+        B.gemm_op(a, a, c, 0, 64, 64),                       # empty
+        B.gemm_op(a, a, c, 64, 64, 64, ldc=32),              # ldc < N
+        B.gemm_op(None, a, c, 64, 64, 64),                   # null operand
+        B.gemm_op(a.view(-1)[1:].data_ptr(), a, c, 8, 8, 8), # misaligned A
+        B.gemm_op(a, a, c, 64, 64, 64, tile=77),             # unknown tile
+        B.gemm_op(a, a, c, 64, 64, 64, tile=B.TILE_SKINNY),  # skinny needs M <= 32 and TRANS_B
+    ]
+    for op in cases:
+        with pytest.raises(B.LithosError) as e:
+            B.lithos_launch_atomized(ctx(), op)
+        assert e.value.code == B.EINVAL
+    op = B.gemm_op(a, a, c, 64, 64, 64, tile=64)
+    with pytest.raises(B.LithosError):
+        B.lithos_launch_atomized(ctx(), op, grid=(3, 1, 1))   # grid with another total
+    with pytest.raises(B.LithosError):
+        B.lithos_launch_atom(ctx(), op, 0, 2)                 # beyond the single block
+    small = counters(0 + 1)[:0]
+    B.lithos_launch_atomized(ctx(), op, grid=(1, 1, 1))       # same total, other factorisation: fine
+    B.lithos_partition_sync(ctx(), None)

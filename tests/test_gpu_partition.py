@@ -1,0 +1,84 @@
+"""CU-masked queues: a masked launch stays inside its CUs, disjoint masks use
+disjoint CUs, every die is covered, and the right-size sweep returns a curve."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rightsize as R
+from paper_2504_15465_amd import binding as B
+from gpu_util import ctx
+
+pytestmark = pytest.mark.gpu
+
+
+def cu_ids(xcd, hwid):
+    """(die, shader engine, array, CU) from the hardware id register."""
+    return set(zip(xcd.tolist(), ((hwid >> 13) & 7).tolist(), ((hwid >> 12) & 1).tolist(), ((hwid >> 8) & 15).tolist()))
+
+
+def test_device_shape():
+    info = B.lithos_device_info(ctx())
+    assert info.n_cu == 256 and info.n_xcd == 8 and info.cu_per_xcd == 32
+    assert info.arch.decode().startswith("gfx950")
+
+
+def test_masked_launch_stays_in_its_cus_and_masks_are_disjoint():
+    c = ctx()
+    m_hp = B.lithos_make_mask(c, 64, B.MASK_STRIPED, 0)
+    m_be = B.lithos_make_mask(c, 192, B.MASK_STRIPED, 64)
+    assert not np.any(m_hp & m_be)
+    assert sum(bin(int(w)).count("1") for w in m_hp) == 64
+    p_hp, p_be = B.lithos_create_partition(c, m_hp), B.lithos_create_partition(c, m_be)
+    try:
+        assert B.lithos_partition_cus(p_hp) == 64 and B.lithos_partition_cus(p_be) == 192
+        x1, h1 = B.lithos_probe_partition(c, p_hp, 4096)
+        x2, h2 = B.lithos_probe_partition(c, p_be, 8192)
+        x0, h0 = B.lithos_probe_partition(c, None, 8192)
+        s1, s2, s0 = cu_ids(x1, h1), cu_ids(x2, h2), cu_ids(x0, h0)
+        assert len(s1) <= 64 and len(s2) <= 192 and len(s0) <= 256
+        assert len(s1) >= 56 and len(s2) >= 170          # nearly every CU of the mask was used
+        assert not (s1 & s2)                              # disjoint masks -> disjoint CUs
+        assert s1 <= s0 and s2 <= s0
+        # striped masks put the same number of CUs on every die
+        for s, per_die in ((s1, 8), (s2, 24)):
+            by_die = {}
+            for die, *_ in s:
+                by_die[die] = by_die.get(die, 0) + 1
+            assert sorted(by_die) == list(range(8))
+            assert max(by_die.values()) <= per_die
+    finally:
+        B.lithos_destroy_partition(p_hp)
+        B.lithos_destroy_partition(p_be)
+
+
+def test_masks_that_empty_a_die_or_are_empty_are_refused():
+    c = ctx()
+    with pytest.raises(B.LithosError) as e:
+        B.lithos_create_partition(c, [0] * 8)
+    assert e.value.code == B.EMASK
+    whole = B.lithos_make_mask(c, 32, B.MASK_WHOLE_XCD, 0)     # all of die 0, nothing elsewhere
+    with pytest.raises(B.LithosError) as e:
+        B.lithos_create_partition(c, whole)
+    assert e.value.code == B.EMASK
+    with pytest.raises(B.LithosError):
+        B.lithos_make_mask(c, 300)
+    with pytest.raises(B.LithosError):
+        B.lithos_make_mask(c, 8, B.MASK_STRIPED, 252)
+
+
+def test_rightsize_sweep_on_a_spin_kernel_and_selection_rule():
+    """A kernel of 256 blocks that each hold a CU for 50 us: latency ~ 50 us * ceil(256/CUs)."""
+    c = ctx()
+    op = B.spin_op(256, 5000)
+    r = B.lithos_rightsize(c, op, 32, 256, 32, 2, 7, 0.04)
+    cus = list(r.cus[: r.n_points])
+    lat = list(r.median_us[: r.n_points])
+    assert cus == list(range(32, 257, 32))
+    assert 40.0 < lat[-1] < 120.0                       # one wave of blocks on the full GPU
+    assert lat[0] > 5 * lat[-1]                         # 32 CUs need 8 waves
+    assert r.chosen_cus == R.select_from_sweep(cus, lat, 0.04)
+    assert r.occupancy_bound_cus == 256
+    m, b = r.model_m, r.model_b
+    assert abs(m / cus[0] + b - lat[0]) < 1e-6 * lat[0] and abs(m / cus[-1] + b - lat[-1]) < 1e-6 * lat[-1]
+    with pytest.raises(B.LithosError):
+        B.lithos_rightsize(c, op, 8, 512, 8, 1, 3, 0.04)

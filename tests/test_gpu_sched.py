@@ -1,0 +1,120 @@
+"""Two tenants on CU-masked queues under the spatial scheduler: results stay
+bit-exact while kernels are cut in atoms and CUs are stolen and handed back."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_15465_amd import binding as B
+from paper_2504_15465_amd import inputs
+from paper_2504_15465_amd.models import MlpChain, run_ops
+from gpu_util import bits_equal, dev_bits, nan_like
+
+pytestmark = pytest.mark.gpu
+
+
+def make_world(cfg):
+    c = B.lithos_init(0, cfg)
+    p_hp = B.lithos_create_partition(c, B.lithos_make_mask(c, 64, B.MASK_STRIPED, 0))
+    p_be = B.lithos_create_partition(c, B.lithos_make_mask(c, 192, B.MASK_STRIPED, 64))
+    return c, p_hp, p_be
+
+
+def drop_world(c, parts, tenants):
+    for t in tenants:
+        B.lithos_tenant_destroy(t)
+    for p in parts:
+        B.lithos_destroy_partition(p)
+    B.lithos_shutdown(c)
+
+
+@pytest.mark.parametrize("steal,atomize", [(1, 1), (1, 0), (0, 1), (0, 0)])
+def test_stacked_tenants_bit_exact_and_stats(steal, atomize):
+    cfg = B.Config.default(atom_duration_us=100.0, max_outstanding=2, max_outstanding_hp=16, steal=steal, atomize=atomize)
+    c, p_hp, p_be = make_world(cfg)
+    t_hp = B.lithos_tenant_create(c, B.CLASS_HP, p_hp)
+    t_be = B.lithos_tenant_create(c, B.CLASS_BE, p_be)
+    try:
+        # best-effort: 4096^3 GEMM (256 tiles of 256x256), reference from a plain launch
+        m = 4096
+        a_bits, b_bits = inputs.gemm_operands(m, m, m, seed=4)
+        a, b = dev_bits(a_bits), dev_bits(b_bits)
+        c_ref = nan_like((m, m), torch.bfloat16)
+        B.lithos_launch_atomized(c, B.gemm_op(a, b, c_ref, m, m, m, tile=256))
+        B.lithos_partition_sync(c, None)
+        c_be = nan_like((m, m), torch.bfloat16)
+        be_op = B.gemm_op(a, b, c_be, m, m, m, tile=256)
+        # high-priority: a small MLP
+        layers = inputs.mlp_params(2, 1024, seed=1)
+        x = inputs.mlp_requests(pool=1, batch=8, hidden=1024, seed=2)[0]
+        chain = MlpChain(layers, 8)
+        chain.set_input(x)
+        run_ops(c, chain.ops(), p_hp)
+        hp_ref = chain.out.clone()
+        hp_ops = chain.ops()
+
+        drv = B.lithos_drive_closed_loop_start(t_be, [be_op], depth=2)
+        time.sleep(0.05)
+        for i in range(30):
+            chain.out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            for op in hp_ops:
+                B.lithos_submit(t_hp, op)
+            B.lithos_sync(t_hp)
+            assert bits_equal(chain.out, hp_ref), "request %d" % i
+            time.sleep(0.002)
+        iters, secs = B.lithos_drive_closed_loop_stop(drv)
+        B.lithos_sync(t_be)
+        assert iters >= 3
+        assert bits_equal(c_be, c_ref)
+        s_be, s_hp = B.lithos_tenant_stats(t_be), B.lithos_tenant_stats(t_hp)
+        assert s_hp.kernels == 30 * len(hp_ops)
+        assert s_be.kernels >= iters
+        if atomize:
+            assert s_be.atoms > s_be.kernels          # the long GEMM was cut
+        else:
+            assert s_be.atoms == s_be.kernels
+        assert s_hp.atoms == s_hp.kernels             # microsecond kernels stay whole
+        if steal:
+            assert s_be.stolen_atoms > 0              # idle high-priority CUs were lent
+        else:
+            assert s_be.stolen_atoms == 0 and s_hp.stolen_atoms == 0
+    finally:
+        drop_world(c, [p_hp, p_be], [t_hp, t_be])
+
+
+def test_open_loop_driver_and_passthrough_tenants():
+    c = B.lithos_init(0, None)
+    t_hp = B.lithos_tenant_create(c, B.CLASS_HP, None)       # pass-through: plain queue, no atoms
+    try:
+        ops = [B.spin_op(8, 1000)]                            # ~10 us per request
+        arr = inputs.poisson_arrivals(2000.0, 200, seed=3)
+        lat = B.lithos_drive_open_loop(t_hp, [ops], arr)
+        assert lat.shape == (200,) and np.all(lat > 5.0) and np.median(lat) < 500.0
+        s = B.lithos_tenant_stats(t_hp)
+        assert s.kernels == 200 and s.atoms == 200
+    finally:
+        B.lithos_tenant_destroy(t_hp)
+        B.lithos_shutdown(c)
+
+
+def test_overlapping_quotas_and_shutdown_with_tenants_are_refused():
+    c = B.lithos_init(0, None)
+    p1 = B.lithos_create_partition(c, B.lithos_make_mask(c, 64, B.MASK_STRIPED, 0))
+    p2 = B.lithos_create_partition(c, B.lithos_make_mask(c, 64, B.MASK_STRIPED, 32))
+    t1 = B.lithos_tenant_create(c, B.CLASS_HP, p1)
+    try:
+        with pytest.raises(B.LithosError) as e:
+            B.lithos_tenant_create(c, B.CLASS_BE, p2)
+        assert e.value.code == B.EMASK
+        with pytest.raises(B.LithosError) as e:
+            B.lithos_shutdown(c)
+        assert e.value.code == B.ESTATE
+        with pytest.raises(B.LithosError):
+            B.lithos_submit(t1, B.make_op(99, (1, 1)))
+    finally:
+        B.lithos_tenant_destroy(t1)
+        B.lithos_destroy_partition(p1)
+        B.lithos_destroy_partition(p2)
+        B.lithos_shutdown(c)
