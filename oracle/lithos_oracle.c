@@ -89,11 +89,13 @@ void lo_round_bf16_array(const double *in, double *out, size_t n)
 /* C[i,j] = sum_{k=0}^{K-1} op(A)[i,k] * op(B)[k,j], k ascending, fp64.
  * op(A)[i,k] = ta ? A[k*lda+i] : A[i*lda+k]
  * op(B)[k,j] = tb ? B[j*ldb+k] : B[k*ldb+j]
- * A and B are bf16 bit patterns (the very bits the GPU kernel reads); each
- * product of two bf16 values is exact in fp64, so the only rounding is the
- * running sum.  Rows are independent and may run on separate threads. */
+ * B is bf16 bit patterns (the very bits the GPU kernel reads).  A is given as
+ * fp64 values that are exactly the GPU's activations (widened bf16 bits, or
+ * widened fp32 for kernels that read fp32 activations); a product of an fp32
+ * and a bf16 value is exact in fp64, so the only rounding is the running sum.
+ * Rows are independent and may run on separate threads. */
 int lo_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K,
-            const uint16_t *A, int64_t lda,
+            const double *A, int64_t lda,
             const uint16_t *B, int64_t ldb,
             double *C, int64_t ldc)
 {
@@ -103,7 +105,7 @@ int lo_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K,
         for (int64_t j = 0; j < N; ++j) {
             double s = 0.0;
             for (int64_t k = 0; k < K; ++k) {
-                double a = lo_bf16_to_f64(ta ? A[k * lda + i] : A[i * lda + k]);
+                double a = ta ? A[k * lda + i] : A[i * lda + k];
                 double b = lo_bf16_to_f64(tb ? B[j * ldb + k] : B[k * ldb + j]);
                 s += a * b;
             }
@@ -118,7 +120,7 @@ int lo_gemm(int ta, int tb, int64_t M, int64_t N, int64_t K,
  * Every C[i,j] still receives its K products in ascending k, so the result
  * is bit-identical to lo_gemm; it exists only so full-size checks finish. */
 int lo_gemm_rowsweep(int ta, int64_t M, int64_t N, int64_t K,
-                     const uint16_t *A, int64_t lda,
+                     const double *A, int64_t lda,
                      const uint16_t *B, int64_t ldb,
                      double *C, int64_t ldc)
 {
@@ -128,7 +130,7 @@ int lo_gemm_rowsweep(int ta, int64_t M, int64_t N, int64_t K,
         double *c = C + i * ldc;
         for (int64_t j = 0; j < N; ++j) c[j] = 0.0;
         for (int64_t k = 0; k < K; ++k) {
-            double a = lo_bf16_to_f64(ta ? A[k * lda + i] : A[i * lda + k]);
+            double a = ta ? A[k * lda + i] : A[i * lda + k];
             const uint16_t *b = B + k * ldb;
             for (int64_t j = 0; j < N; ++j) c[j] += a * lo_bf16_to_f64(b[j]);
         }

@@ -32,19 +32,16 @@ def _bits(x64):
 def mlp_forward(x_bits, layers, eps: float = 1e-5):
     """h <- LN(GELU(h @ W + b)) per layer.
 
-    x_bits [B,H] bf16 bits.  GELU output is an fp32 edge, LayerNorm output is
-    a bf16 edge (it feeds the next GEMM) except after the last layer (fp32).
-    Returns fp64 [B,H].
+    x_bits [B,H] bf16 bits.  Every edge inside the chain is fp32 on the GPU
+    (the weight-streaming GEMM reads fp32 activations), so nothing is rounded
+    here after the input.  Returns fp64 [B,H].
     """
-    h_bits = np.asarray(x_bits, dtype=np.uint16)
-    out = None
-    for i, L in enumerate(layers):
-        u = ops.gemm(h_bits, L["w"])
+    h = ops.bf16_to_f64(np.asarray(x_bits, dtype=np.uint16))
+    for L in layers:
+        u = ops.gemm(h, L["w"])
         act = ops.bias_act(u, L["b"].astype(np.float64), gelu=True)      # fp32 edge
-        out = ops.layernorm(act, L["gamma"].astype(np.float64), L["beta"].astype(np.float64), eps)
-        if i + 1 < len(layers):
-            h_bits = _bits(out)                                          # bf16 edge
-    return out
+        h = ops.layernorm(act, L["gamma"].astype(np.float64), L["beta"].astype(np.float64), eps)  # fp32 edge
+    return h
 
 
 # -------------------------------------------------------------- encoder ----
@@ -85,32 +82,34 @@ def decoder_decode_step(x32, layers, kcache_bits, vcache_bits, n_q: int, n_kv: i
     x32 [B,H] fp32 hidden state of the current token (position ``pos``).
     kcache_bits / vcache_bits: per-layer lists of [B, pos, n_kv, d] bf16 bits
     holding the ``pos`` cached positions; the current token's key/value are
-    appended, so attention covers pos+1 keys.  Weights: w_qkv [H,(n_q+2 n_kv) d],
-    w_o [n_q d, H], w_gu [H, 2F] (gate columns then up columns), w_d [F,H].
-    Returns fp64 [B,H] (no final norm).
+    rounded to bf16 (they are appended to the bf16 cache), so attention covers
+    pos+1 bf16 keys.  Every other edge is fp32 on the GPU (all GEMMs are the
+    weight-streaming kind that reads fp32 activations).
+    Weights: w_qkv [H,(n_q+2 n_kv) d], w_o [n_q d, H], w_gu [H, 2F] (gate
+    columns then up columns), w_d [F,H].  Returns fp64 [B,H] (no final norm).
     """
     x = np.asarray(x32, dtype=np.float64)
     B, H = x.shape
     d = H // n_q
     positions = np.full((B,), pos, dtype=np.int64)
     for li, L in enumerate(layers):
-        n1 = _bits(ops.rmsnorm(x, L["rms1"].astype(np.float64), eps))    # bf16 edge
-        qkv = ops.round_bf16(ops.gemm(n1, L["w_qkv"]))                   # bf16 edge
+        n1 = ops.rmsnorm(x, L["rms1"].astype(np.float64), eps)
+        qkv = ops.gemm(n1, L["w_qkv"])
         q = qkv[:, : n_q * d].reshape(B, n_q, d)
         k = qkv[:, n_q * d: (n_q + n_kv) * d].reshape(B, n_kv, d)
         v = qkv[:, (n_q + n_kv) * d:].reshape(B, n_kv, d)
-        q = ops.round_bf16(ops.rope(q, positions, theta))                # bf16 edge
-        k = ops.round_bf16(ops.rope(k, positions, theta))                # bf16 edge (cache slot)
+        q = ops.rope(q, positions, theta)
+        k = ops.round_bf16(ops.rope(k, positions, theta))               # bf16 edge (cache slot)
+        v = ops.round_bf16(v)                                            # bf16 edge (cache slot)
         kc = ops.bf16_to_f64(kcache_bits[li])                            # [B,pos,n_kv,d]
         vc = ops.bf16_to_f64(vcache_bits[li])
         k_all = np.concatenate([kc, k[:, None]], axis=1)
         v_all = np.concatenate([vc, v[:, None]], axis=1)
         att = ops.attention(q[:, None], k_all, v_all, 1.0 / math.sqrt(d))  # [B,1,n_q,d]
-        att_bits = _bits(att.reshape(B, n_q * d))                        # bf16 edge
-        x = x + ops.gemm(att_bits, L["w_o"])                             # fp32 edge
-        n2 = _bits(ops.rmsnorm(x, L["rms2"].astype(np.float64), eps))    # bf16 edge
-        gu = ops.round_bf16(ops.gemm(n2, L["w_gu"]))                     # bf16 edge
+        x = x + ops.gemm(att.reshape(B, n_q * d), L["w_o"])
+        n2 = ops.rmsnorm(x, L["rms2"].astype(np.float64), eps)
+        gu = ops.gemm(n2, L["w_gu"])
         F = gu.shape[1] // 2
-        act = _bits(ops.silu_mul(gu[:, :F], gu[:, F:]))                  # bf16 edge
-        x = x + ops.gemm(act, L["w_d"])                                  # fp32 edge
+        act = ops.silu_mul(gu[:, :F], gu[:, F:])
+        x = x + ops.gemm(act, L["w_d"])
     return x

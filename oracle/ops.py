@@ -97,14 +97,17 @@ def round_bf16(x) -> np.ndarray:
 
 # ------------------------------------------------------------------ GEMM ---
 
-def gemm(a_bits, b_bits, ta: bool = False, tb: bool = False, fast: bool = True) -> np.ndarray:
-    """fp64 C = op(A) @ op(B) on bf16 bit patterns, ascending-k sums.
+def gemm(a, b_bits, ta: bool = False, tb: bool = False, fast: bool = True) -> np.ndarray:
+    """fp64 C = op(A) @ op(B), ascending-k sums.
 
-    ``a_bits`` is [M,K] (or [K,M] when ``ta``), ``b_bits`` is [K,N] (or [N,K]
-    when ``tb``).  ``fast`` picks the (i,k,j) loop order for non-transposed B;
-    each element's summation order is unchanged, so the result is bit-equal.
+    ``a`` is [M,K] (or [K,M] when ``ta``): bf16 bit patterns (uint16) or the
+    activations' values as floats (for kernels that read fp32 activations).
+    ``b_bits`` is [K,N] (or [N,K] when ``tb``), bf16 bit patterns.  ``fast``
+    picks the (i,k,j) loop order for non-transposed B; each element's
+    summation order is unchanged, so the result is bit-equal.
     """
-    A, pA = _u(a_bits)
+    a = np.asarray(a)
+    A, pA = _d(bf16_to_f64(a) if a.dtype == np.uint16 else a)
     B, pB = _u(b_bits)
     if A.ndim != 2 or B.ndim != 2:
         raise ValueError("gemm expects 2-D operands")

@@ -139,6 +139,8 @@ def make_op(kind, dims=(), flags=0, tile=0, ld=(), fparam=(), inputs=(), outputs
         op.inp[i] = _ptr(t)
     for i, t in enumerate(outputs):
         op.out[i] = _ptr(t)
+    # the descriptor holds raw pointers: keep the tensors alive as long as it lives
+    op._keep = (tuple(inputs), tuple(outputs))
     return op
 
 
@@ -148,6 +150,8 @@ def gemm_op(a, b, c, m, n, k, ta=False, tb=False, bias=None, gelu=False, residua
     flags |= (F_GELU if gelu else 0) | (F_RESIDUAL if residual is not None else 0)
     if isinstance(c, torch.Tensor) and c.dtype == torch.float32:
         flags |= F_OUT_F32
+    if isinstance(a, torch.Tensor) and a.dtype == torch.float32:
+        flags |= F_IN_F32
     lda = lda if lda is not None else (m if ta else k)
     ldb = ldb if ldb is not None else (k if tb else n)
     ldc = ldc if ldc is not None else n

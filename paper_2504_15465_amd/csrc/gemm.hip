@@ -3,9 +3,10 @@
 // Two kernel families:
 //  * gemm_tile_kernel  - MFMA (v_mfma_f32_32x32x16_bf16) on LDS-staged tiles of
 //    64x64, 128x128 or 256x256 outputs, BK = 64, 4 wavefronts per workgroup;
-//  * gemm_skinny_kernel - M <= 32 rows against a [N,K] weight matrix: the
-//    weights are streamed once from HBM with 16-byte loads and multiplied on
-//    the vector ALUs (the op is HBM-bound; reshaping it for MFMA buys nothing).
+//  * gemm_skinny_kernel - M <= 32 rows (bf16 or fp32 activations) against a
+//    [N,K] bf16 weight matrix: the weights are streamed once from HBM with
+//    16-byte loads and multiplied on the vector ALUs (the op is HBM-bound;
+//    reshaping it for MFMA buys nothing).
 //
 // Every workgroup computes the output tile named by its LOGICAL block index
 // (LithOS Section 4.4), so a launch of any sub-range of blocks writes exactly
@@ -248,18 +249,77 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 }
 
 // ---- skinny: M <= MT rows, B stored [N,K] ---------------------------------
-// A workgroup owns 16 output columns (4 per wavefront).  x[:, k-chunk] is
-// staged in LDS as bf16; each lane multiplies eight consecutive k of four
-// weight rows with the same eight k of every x row; a butterfly over the 64
-// lanes finishes each dot product.  Lane order and chunk order are fixed, so
-// the result is a pure function of the logical block index.
-template <int MT>
+// A workgroup owns 16 output columns (4 per wavefront) and walks K in stages
+// of KC.  The activations x[:, stage] are staged in LDS (fp32 when the op
+// gives fp32 activations, else bf16); each lane multiplies eight consecutive k
+// of four weight rows with the same eight k of every x row, and a butterfly
+// over the 64 lanes finishes each dot product.  The next stage's x and
+// weights are already in flight (in registers) while the current one is
+// computed.  Lane order and stage order are fixed, so the result is a pure
+// function of the logical block index.
+template <int MT, bool A32>
+struct SkinnyStage {
+    static constexpr int KC0 = (A32 ? 8192 : 16384) / MT;     // 32 KB of x per stage ...
+    static constexpr int KC = KC0 < 512 ? 512 : KC0;          // ... but at least one k-step per lane
+    static constexpr int LDS_BYTES = MT * KC * (A32 ? 4 : 2);
+    static constexpr int XV = LDS_BYTES / 16 / 256;           // 16-byte x registers per thread
+    static constexpr int IT = KC / 512;                       // k-steps per lane per stage
+    static constexpr int NC = 4;
+    uint4 x[XV];
+    uint4 w[IT][NC];
+
+    __device__ __forceinline__ void load(const GemmArgs& g, const uint16_t* const (&wrow)[NC], int k0, int tid, int lane)
+    {
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            int k = k0 + it * 512 + lane * 8;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (k < g.K) v = *reinterpret_cast<const uint4*>(wrow[c] + k);
+                w[it][c] = v;
+            }
+        }
+        constexpr int EPV = A32 ? 4 : 8;                      // elements per 16-byte register
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            int c = tid + i * 256;
+            int m = c / (KC / EPV), kk = (c % (KC / EPV)) * EPV;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (m < g.M && k0 + kk < g.K) {
+                if constexpr (A32) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(g.A) + (int64_t)m * g.lda + k0 + kk);
+                else v = *reinterpret_cast<const uint4*>(g.A + (int64_t)m * g.lda + k0 + kk);
+            }
+            x[i] = v;
+        }
+    }
+
+    // fp32 layout in LDS: the two halves (k%8 < 4, k%8 >= 4) of every 8-group
+    // live in separate planes, so the 64 lanes read consecutive 16-byte slots.
+    __device__ __forceinline__ void store(void* lds, int tid) const
+    {
+        constexpr int EPV = A32 ? 4 : 8;
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            int c = tid + i * 256;
+            int m = c / (KC / EPV), kk = (c % (KC / EPV)) * EPV;
+            if constexpr (A32) {
+                int grp = kk >> 3, half = (kk >> 2) & 1;
+                reinterpret_cast<uint4*>(lds)[(m * KC + half * (KC / 2)) / 4 + grp] = x[i];
+            } else {
+                reinterpret_cast<uint4*>(lds)[(m * KC + kk) / 8] = x[i];
+            }
+        }
+    }
+};
+
+template <int MT, bool A32>
 __global__ __launch_bounds__(256)
 void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
 {
-    constexpr int KC = 16384 / MT;      // 32 KB of x per stage
-    constexpr int NC = 4;
-    __shared__ __attribute__((aligned(16))) uint16_t xs[MT * KC];
+    using Stage = SkinnyStage<MT, A32>;
+    constexpr int KC = Stage::KC, NC = Stage::NC, IT = Stage::IT;
+    __shared__ __attribute__((aligned(16))) unsigned char xs_raw[Stage::LDS_BYTES];
 
     const uint32_t L = atom_logical_block(atom);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -275,22 +335,20 @@ void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
 #pragma unroll
     for (int c = 0; c < NC; ++c) wrow[c] = g.B + (int64_t)min(nbase + c, g.N - 1) * g.ldb;
 
+    Stage cur, nxt;
+    cur.load(g, wrow, 0, tid, lane);
     for (int k0 = 0; k0 < g.K; k0 += KC) {
-        // stage x[0..MT) x [k0, k0+KC)
-        for (int c = tid; c < MT * KC / 8; c += 256) {
-            int m = c / (KC / 8), kk = (c % (KC / 8)) * 8;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (m < g.M && k0 + kk < g.K) v = *reinterpret_cast<const uint4*>(g.A + (int64_t)m * g.lda + k0 + kk);
-            *reinterpret_cast<uint4*>(xs + m * KC + kk) = v;
-        }
+        cur.store(xs_raw, tid);
         __syncthreads();
-        for (int kk = lane * 8; kk < KC; kk += 512) {
-            if (k0 + kk >= g.K) break;
+        if (k0 + KC < g.K) nxt.load(g, wrow, k0 + KC, tid, lane);
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int kk = it * 512 + lane * 8;          // offset inside the stage
             float wf[NC][8];
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                uint4 v = *reinterpret_cast<const uint4*>(wrow[c] + k0 + kk);
-                uint32_t u[4] = {v.x, v.y, v.z, v.w};
+                const uint4 v = cur.w[it][c];
+                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     wf[c][2 * p] = __uint_as_float(u[p] << 16);
@@ -299,13 +357,21 @@ void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
             }
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
-                uint4 v = *reinterpret_cast<const uint4*>(xs + m * KC + kk);
-                uint32_t u[4] = {v.x, v.y, v.z, v.w};
                 float xf[8];
+                if constexpr (A32) {
+                    const float* xl = reinterpret_cast<const float*>(xs_raw);
+                    const float4 lo = *reinterpret_cast<const float4*>(xl + m * KC + (kk >> 3) * 4);
+                    const float4 hi = *reinterpret_cast<const float4*>(xl + m * KC + KC / 2 + (kk >> 3) * 4);
+                    xf[0] = lo.x; xf[1] = lo.y; xf[2] = lo.z; xf[3] = lo.w;
+                    xf[4] = hi.x; xf[5] = hi.y; xf[6] = hi.z; xf[7] = hi.w;
+                } else {
+                    const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(xs_raw) + m * KC + kk);
+                    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    xf[2 * p] = __uint_as_float(u[p] << 16);
-                    xf[2 * p + 1] = __uint_as_float(u[p] & 0xffff0000u);
+                    for (int p = 0; p < 4; ++p) {
+                        xf[2 * p] = __uint_as_float(u[p] << 16);
+                        xf[2 * p + 1] = __uint_as_float(u[p] & 0xffff0000u);
+                    }
                 }
 #pragma unroll
                 for (int c = 0; c < NC; ++c)
@@ -314,6 +380,7 @@ void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
             }
         }
         __syncthreads();
+        cur = nxt;
     }
 
 #pragma unroll
@@ -348,12 +415,12 @@ static gemm_fn tile_fn(int tile, bool ta, bool tb)
 #undef PICK
 }
 
-static gemm_fn variant_fn(int variant, bool ta, bool tb)
+static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32)
 {
     switch (variant) {
-    case V_SKINNY8: return (gemm_fn)gemm_skinny_kernel<8>;
-    case V_SKINNY16: return (gemm_fn)gemm_skinny_kernel<16>;
-    case V_SKINNY32: return (gemm_fn)gemm_skinny_kernel<32>;
+    case V_SKINNY8: return a32 ? (gemm_fn)gemm_skinny_kernel<8, true> : (gemm_fn)gemm_skinny_kernel<8, false>;
+    case V_SKINNY16: return a32 ? (gemm_fn)gemm_skinny_kernel<16, true> : (gemm_fn)gemm_skinny_kernel<16, false>;
+    case V_SKINNY32: return a32 ? (gemm_fn)gemm_skinny_kernel<32, true> : (gemm_fn)gemm_skinny_kernel<32, false>;
     case V_TILE64: return tile_fn(64, ta, tb);
     case V_TILE128: return tile_fn(128, ta, tb);
     default: return tile_fn(256, ta, tb);
@@ -363,7 +430,7 @@ static gemm_fn variant_fn(int variant, bool ta, bool tb)
 int gemm_plan(const lithos_op_t& op, OpPlan* plan)
 {
     const int64_t M = op.dim[0], N = op.dim[1], K = op.dim[2];
-    const bool ta = op.flags & LITHOS_F_TRANS_A, tb = op.flags & LITHOS_F_TRANS_B;
+    const bool ta = op.flags & LITHOS_F_TRANS_A, tb = op.flags & LITHOS_F_TRANS_B, a32 = op.flags & LITHOS_F_IN_F32;
     if (M <= 0 || N <= 0 || K <= 0 || M > (1 << 30) || N > (1 << 30) || K > (1 << 30))
         return fail(LITHOS_EINVAL, "gemm: M,N,K must be positive (got %lld,%lld,%lld)", (long long)M, (long long)N, (long long)K);
     if (K % 8) return fail(LITHOS_EINVAL, "gemm: K must be a multiple of 8 (got %lld)", (long long)K);
@@ -381,6 +448,8 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         if (ldr < N) return fail(LITHOS_EINVAL, "gemm: ldr smaller than N");
     }
     int tile = op.tile;
+    if (a32 && !(M <= 32 && tb && !ta && (tile == 0 || tile == LITHOS_TILE_SKINNY)))
+        return fail(LITHOS_EINVAL, "gemm: fp32 activations (IN_F32) are only taken by the skinny kernel (M <= 32, TRANS_B)");
     if (tile == 0) {
         if (M <= 32 && tb && !ta) tile = LITHOS_TILE_SKINNY;
         else if (((M + 255) / 256) * ((N + 255) / 256) >= 256) tile = 256;
@@ -390,6 +459,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
     int variant;
     if (tile == LITHOS_TILE_SKINNY) {
         if (M > 32 || !tb || ta) return fail(LITHOS_EINVAL, "gemm: the skinny kernel needs M <= 32, TRANS_B and no TRANS_A");
+        if (a32 && (lda % 4)) return fail(LITHOS_EINVAL, "gemm: fp32 activations need lda %% 4 == 0");
         variant = M <= 8 ? V_SKINNY8 : M <= 16 ? V_SKINNY16 : V_SKINNY32;
         plan->grid = {(uint32_t)((N + 15) / 16), 1, 1};
     } else if (tile == 64 || tile == 128 || tile == 256) {
@@ -402,7 +472,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
     plan->threads = 256;
     plan->variant = variant;
     int occ = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void*)variant_fn(variant, ta, tb), 256, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void*)variant_fn(variant, ta, tb, a32), 256, 0);
     plan->wg_per_cu = (e == hipSuccess && occ > 0) ? (uint32_t)occ : 1u;
     if (e != hipSuccess) (void)hipGetLastError();
     return LITHOS_OK;
@@ -420,7 +490,7 @@ int gemm_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     g.lda = op.ld[0]; g.ldb = op.ld[1]; g.ldc = op.ld[2]; g.ldr = op.ld[3];
     g.flags = op.flags;
     g.tiles_m = plan.grid.y; g.tiles_n = plan.grid.x;
-    gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B);
+    gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B, op.flags & LITHOS_F_IN_F32);
     LITHOS_HIP(launch_kernel(fn, dim3(atom.n), dim3(256), s, g, atom));
     return LITHOS_OK;
 }

@@ -235,9 +235,14 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RowArgs a, AtomArgs atom)
 }
 
 // ---- spin: every block waits `ticks` of the constant 100 MHz counter -------
-__global__ __launch_bounds__(64) void spin_kernel(uint64_t ticks, AtomArgs atom)
+// 1024 threads and 64 KB of LDS per block: exactly two blocks fit on a CU, so
+// the kernel's latency is ticks * ceil(blocks / (2 * CUs)) - a known scaling
+// curve for scheduler and right-sizing tests.
+__global__ __launch_bounds__(1024) void spin_kernel(uint64_t ticks, AtomArgs atom)
 {
-    (void)atom_logical_block(atom);
+    __shared__ uint32_t pad[16384];
+    const uint32_t L = atom_logical_block(atom);
+    if (threadIdx.x == 0) reinterpret_cast<volatile uint32_t*>(pad)[L & 16383] = L;
     const uint64_t t0 = wall_clock64();
     while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(8);
 }
@@ -306,8 +311,8 @@ int rowops_plan(const lithos_op_t& op, OpPlan* plan)
     case LITHOS_OP_SPIN:
         if (op.dim[1] < 0 || op.dim[1] > 100000000) return fail(LITHOS_EINVAL, "spin: ticks must be in [0, 1e8] (1 s)");
         blocks = rows;
-        plan->threads = 64;
-        plan->wg_per_cu = 1;
+        plan->threads = 1024;
+        plan->wg_per_cu = 2;
         break;
     default:
         return fail(LITHOS_EINVAL, "unknown row op kind %d", op.kind);

@@ -5,13 +5,15 @@ order and dtype of every edge.  All arithmetic runs in liblithos kernels.
 
 Edge dtypes (what is stored between two kernels):
 
-* MLP layer        GEMM(+bias+GELU) -> fp32; LayerNorm -> bf16 (fp32 after the last layer)
+* MLP layer        GEMM(+bias+GELU) -> fp32; LayerNorm -> fp32.  The batch is
+                   small, so the GEMM is the weight-streaming kind, which
+                   reads fp32 activations against bf16 weights.
 * encoder layer    QKV GEMM -> bf16; attention -> bf16; out-proj(+bias+residual) -> fp32;
                    LayerNorm -> fp32 + bf16 copy; FFN1(+bias+GELU) -> bf16;
                    FFN2(+bias+residual) -> fp32; LayerNorm -> fp32 + bf16 copy
-* decoder layer    RMSNorm -> bf16; QKV GEMM -> bf16; RoPE in place (+cache append);
-                   attention -> bf16; o-proj(+residual) -> fp32; RMSNorm -> bf16;
-                   gate/up GEMM -> bf16; SiLU-gate -> bf16; down(+residual) -> fp32
+* decoder layer    every edge fp32 (weight-streaming GEMMs), except the
+                   key/value cache, which is bf16: the current token's rotated
+                   key and its value are rounded when appended.
 """
 from __future__ import annotations
 
@@ -42,7 +44,8 @@ class MlpChain:
     """h <- LayerNorm(GELU(h W + b)), n_layers times, batch rows.
 
     Weights are kept [N,K] so that small batches use the weight-streaming
-    GEMM; ``tile`` forces another GEMM variant (then weights stay [K,N])."""
+    GEMM; ``tile`` forces an MFMA tile variant (then weights stay [K,N] and
+    the LayerNorm output feeding the next GEMM is bf16)."""
 
     def __init__(self, layers, batch: int, device="cuda", tile: int = B.TILE_AUTO):
         self.batch = batch
@@ -57,7 +60,8 @@ class MlpChain:
         self.beta = [_f32(L["beta"], device) for L in layers]
         self.x = torch.zeros((Bn, H), dtype=torch.bfloat16, device=device)
         self.act = torch.zeros((Bn, H), dtype=torch.float32, device=device)
-        self.h = [torch.zeros((Bn, H), dtype=torch.bfloat16, device=device) for _ in range(2)]
+        hdt = torch.float32 if self.skinny else torch.bfloat16
+        self.h = [torch.zeros((Bn, H), dtype=hdt, device=device) for _ in range(2)]
         self.out = torch.zeros((Bn, H), dtype=torch.float32, device=device)
 
     def ops(self, x: torch.Tensor = None) -> List[B.Op]:
@@ -79,7 +83,11 @@ class MlpChain:
 
 
 def run_ops(ctx, ops, part=None, atom_blocks=0):
-    """Launch a chain's operators in order on one partition and wait."""
+    """Launch a chain's operators in order on one partition and wait.
+
+    torch's own work (fills, copies) runs on torch's stream, the library's on
+    its CU-masked queues: torch is drained first so the two cannot race."""
+    torch.cuda.synchronize()
     for op in ops:
         B.lithos_launch_atomized(ctx, op, (0, 0, 0), atom_blocks, part, None)
     B.lithos_partition_sync(ctx, part)

@@ -6,17 +6,18 @@ import pytest
 import torch
 
 from oracle import models as OM
+from oracle import ops as O
 from paper_2504_15465_amd import binding as B
 from paper_2504_15465_amd import inputs
 from paper_2504_15465_amd.models import MlpChain, run_ops
-from gpu_util import bits_equal, ctx
+from gpu_util import bits_equal, ctx, dev_bits, nan_like, rel_fro
 
 pytestmark = pytest.mark.gpu
 
 E2E_TOL = 1e-2
 
 
-@pytest.mark.parametrize("hidden,batch,n_layers", [(4096, 8, 6), (512, 5, 3)])
+@pytest.mark.parametrize("hidden,batch,n_layers", [(4096, 8, 6), (512, 5, 3), (1024, 16, 2), (1024, 32, 2)])
 def test_mlp_chain_matches_oracle(hidden, batch, n_layers):
     layers = inputs.mlp_params(n_layers, hidden, seed=1)
     reqs = inputs.mlp_requests(pool=2, batch=batch, hidden=hidden, seed=2)
@@ -30,6 +31,7 @@ def test_mlp_chain_matches_oracle(hidden, batch, n_layers):
             ref = OM.mlp_forward(reqs[r], layers)
             err = np.abs(out_full.cpu().numpy().astype(np.float64) - ref).max()
             assert err <= E2E_TOL, err
+            assert err <= 1e-4, err          # fp32 edges throughout: far inside the bar
             chain.out.fill_(float("nan"))
             run_ops(ctx(), chain.ops(), part, atom_blocks=5)
             assert bits_equal(chain.out, out_full)
@@ -37,12 +39,23 @@ def test_mlp_chain_matches_oracle(hidden, batch, n_layers):
         B.lithos_destroy_partition(part)
 
 
-def test_mlp_chain_tile_kernel_variant_agrees():
-    """The same model through the 64x64 MFMA tile GEMM ([K,N] weights) stays within the bar."""
-    layers = inputs.mlp_params(2, 1024, seed=1)
-    x = inputs.mlp_requests(pool=1, batch=8, hidden=1024, seed=2)[0]
-    chain = MlpChain(layers, 8, tile=B.TILE_64)
-    chain.set_input(x)
-    run_ops(ctx(), chain.ops())
-    ref = OM.mlp_forward(x, layers)
-    assert np.abs(chain.out.cpu().numpy().astype(np.float64) - ref).max() <= E2E_TOL
+@pytest.mark.parametrize("m,n,k", [(8, 4096, 4096), (16, 1000, 520), (32, 2048, 1536), (3, 72, 8)])
+def test_skinny_gemm_with_fp32_activations(m, n, k):
+    x32 = inputs.normal_f32((m, k), 31)
+    w_bits = inputs.normal_bits((n, k), 32, 0.05)
+    ref = O.gemm(x32.astype(np.float64), w_bits, tb=True)
+    c = nan_like((m, n), torch.float32)
+    op = B.gemm_op(torch.from_numpy(x32).cuda(), dev_bits(w_bits), c, m, n, k, tb=True)
+    torch.cuda.synchronize()
+    B.lithos_launch_atomized(ctx(), op)
+    B.lithos_partition_sync(ctx(), None)
+    assert rel_fro(c, ref) <= 1e-4
+    ca = nan_like((m, n), torch.float32)
+    torch.cuda.synchronize()
+    B.lithos_launch_atomized(ctx(), B.gemm_op(torch.from_numpy(x32).cuda(), dev_bits(w_bits), ca, m, n, k, tb=True),
+                             (0, 0, 0), 3, None, None)
+    B.lithos_partition_sync(ctx(), None)
+    assert bits_equal(c, ca)
+    # fp32 activations are refused by the MFMA tile kernels
+    with pytest.raises(B.LithosError):
+        B.lithos_launch_atomized(ctx(), B.gemm_op(torch.from_numpy(x32).cuda(), dev_bits(w_bits), c, m, n, k, tb=True, tile=64))

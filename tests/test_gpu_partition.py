@@ -67,9 +67,9 @@ def test_masks_that_empty_a_die_or_are_empty_are_refused():
 
 
 def test_rightsize_sweep_on_a_spin_kernel_and_selection_rule():
-    """A kernel of 256 blocks that each hold a CU for 50 us: latency ~ 50 us * ceil(256/CUs)."""
+    """512 blocks, two fit on a CU, each holds its slot for 50 us: latency ~ 50 us * ceil(512/(2 CUs))."""
     c = ctx()
-    op = B.spin_op(256, 5000)
+    op = B.spin_op(512, 5000)
     r = B.lithos_rightsize(c, op, 32, 256, 32, 2, 7, 0.04)
     cus = list(r.cus[: r.n_points])
     lat = list(r.median_us[: r.n_points])

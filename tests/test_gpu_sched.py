@@ -41,6 +41,7 @@ def test_stacked_tenants_bit_exact_and_stats(steal, atomize):
         a_bits, b_bits = inputs.gemm_operands(m, m, m, seed=4)
         a, b = dev_bits(a_bits), dev_bits(b_bits)
         c_ref = nan_like((m, m), torch.bfloat16)
+        torch.cuda.synchronize()
         B.lithos_launch_atomized(c, B.gemm_op(a, b, c_ref, m, m, m, tile=256))
         B.lithos_partition_sync(c, None)
         c_be = nan_like((m, m), torch.bfloat16)
@@ -54,6 +55,7 @@ def test_stacked_tenants_bit_exact_and_stats(steal, atomize):
         hp_ref = chain.out.clone()
         hp_ops = chain.ops()
 
+        torch.cuda.synchronize()
         drv = B.lithos_drive_closed_loop_start(t_be, [be_op], depth=2)
         time.sleep(0.05)
         for i in range(30):

@@ -35,11 +35,8 @@ def test_mlp_chain_against_torch():
         a = F.gelu(u)                                         # erf form, fp64
         h = F.layer_norm(a, (64,), torch.from_numpy(L["gamma"]).double(),
                          torch.from_numpy(L["beta"]).double(), 1e-5)
-        if i + 1 < len(layers):
-            h = bf(h)
-    # bf16 edges inside: allow a few ulp-flips propagated through later layers
-    assert np.abs(got - h.numpy()).max() < 2e-2
-    assert np.median(np.abs(got - h.numpy())) < 1e-6
+    # no rounding inside the chain: the two fp64 evaluations agree closely
+    assert np.abs(got - h.numpy()).max() < 1e-10
     assert got.shape == (5, 64)
     # last LayerNorm is an fp32 edge: per-row statistics are those of LN output
     gam = np.stack([layers[-1]["gamma"]] * 5).astype(np.float64)
@@ -88,23 +85,25 @@ def test_decoder_chain_against_torch():
     h = torch.from_numpy(x).double()
     for li, L in enumerate(layers):
         rms = lambda t: t / torch.sqrt((t * t).mean(dim=1, keepdim=True) + 1e-5)
-        n1 = bf(rms(h))
-        qkv = bf(n1 @ w64(L["w_qkv"]))
-        q = bf(rope_t(qkv[:, : n_q * d].reshape(Bn, n_q, d), T))
+        n1 = rms(h)
+        qkv = n1 @ w64(L["w_qkv"])
+        q = rope_t(qkv[:, : n_q * d].reshape(Bn, n_q, d), T)
         k = bf(rope_t(qkv[:, n_q * d:(n_q + n_kv) * d].reshape(Bn, n_kv, d), T))
-        v = qkv[:, (n_q + n_kv) * d:].reshape(Bn, n_kv, d)
+        v = bf(qkv[:, (n_q + n_kv) * d:].reshape(Bn, n_kv, d))
         k_all = torch.cat([w64(ks[li]), k[:, None]], dim=1)        # [B,T+1,n_kv,d]
         v_all = torch.cat([w64(vs[li]), v[:, None]], dim=1)
         k_e = k_all.repeat_interleave(n_q // n_kv, dim=2).permute(0, 2, 1, 3)
         v_e = v_all.repeat_interleave(n_q // n_kv, dim=2).permute(0, 2, 1, 3)
         att = F.scaled_dot_product_attention(q[:, :, None], k_e, v_e)[:, :, 0].reshape(Bn, n_q * d)
-        h = h + bf(att) @ w64(L["w_o"])
-        n2 = bf(rms(h))
-        gu = bf(n2 @ w64(L["w_gu"]))
-        act = bf(F.silu(gu[:, :ffn]) * gu[:, ffn:])
+        h = h + att @ w64(L["w_o"])
+        n2 = rms(h)
+        gu = n2 @ w64(L["w_gu"])
+        act = F.silu(gu[:, :ffn]) * gu[:, ffn:]
         h = h + act @ w64(L["w_d"])
     diff = np.abs(got - h.numpy())
-    assert diff.max() < 2e-2 and np.median(diff) < 1e-6
+    # only the appended key/value are rounded (bf16 cache): a rare double-rounding
+    # difference of one ulp there moves the output by far less than 1e-3
+    assert diff.max() < 1e-3 and np.median(diff) < 1e-9
 
 
 def test_decoder_attends_to_cache_and_current_token():
