@@ -199,6 +199,15 @@ typedef struct lithos_rightsize_result {
 int lithos_rightsize(lithos_ctx_t* ctx, const lithos_op_t* op, int cu_lo, int cu_hi, int cu_step,
                      int warmup, int reps, double slowdown, lithos_rightsize_result_t* out);
 
+/* Time `reps` launches of `op` cut in atoms of atom_blocks (0 = whole) on the
+ * partition's queue (NULL: the unmasked queue), each launch bracketed by
+ * device time stamps on that queue; `warmup` untimed launches first.
+ * Mean and median of the per-launch durations in microseconds.  This is the
+ * measurement behind the atom-overhead figure: (atomized - whole) / whole. */
+int lithos_time_launch(lithos_ctx_t* ctx, const lithos_op_t* op, uint32_t atom_blocks,
+                       const lithos_partition_t* part, int warmup, int reps,
+                       double* mean_us_out, double* median_us_out);
+
 /* ---- tenants and the spatial scheduler (Sections 4.2, 4.3, 4.7) ---------- */
 
 #define LITHOS_CLASS_HP 0

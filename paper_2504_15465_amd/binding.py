@@ -79,7 +79,7 @@ EXPORTS = [
     "lithos_make_mask", "lithos_create_partition", "lithos_destroy_partition", "lithos_partition_cus",
     "lithos_partition_stream", "lithos_probe_partition",
     "lithos_op_grid", "lithos_launch_atomized", "lithos_launch_atom", "lithos_partition_sync",
-    "lithos_debug_block_counters", "lithos_rightsize",
+    "lithos_debug_block_counters", "lithos_rightsize", "lithos_time_launch",
     "lithos_tenant_create", "lithos_tenant_destroy", "lithos_submit", "lithos_sync_mark", "lithos_sync",
     "lithos_poll", "lithos_tenant_stats",
     "lithos_drive_open_loop", "lithos_drive_closed_loop_start", "lithos_drive_closed_loop_stop",
@@ -293,6 +293,14 @@ def lithos_rightsize(ctx, op: Op, cu_lo=8, cu_hi=256, cu_step=8, warmup=5, reps=
     r = RightsizeResult()
     _check(lib().lithos_rightsize(ctx, C.byref(op), cu_lo, cu_hi, cu_step, warmup, reps, C.c_double(slowdown), C.byref(r)))
     return r
+
+
+def lithos_time_launch(ctx, op: Op, atom_blocks=0, part=None, warmup=3, reps=20):
+    """(mean_us, median_us) of `reps` launches, device time stamps."""
+    mean, med = C.c_double(), C.c_double()
+    _check(lib().lithos_time_launch(ctx, C.byref(op), C.c_uint32(atom_blocks), part, int(warmup), int(reps),
+                                    C.byref(mean), C.byref(med)))
+    return mean.value, med.value
 
 
 # ---- tenants ------------------------------------------------------------------------------

@@ -528,3 +528,47 @@ int lithos_rightsize(lithos_ctx_t* ctx, const lithos_op_t* op, int cu_lo, int cu
 }
 
 } // extern "C"
+
+// ---- timing of one (atomized) launch with device time stamps ---------------------
+
+extern "C" int lithos_time_launch(lithos_ctx_t* ctx, const lithos_op_t* op, uint32_t atom_blocks,
+                                  const lithos_partition_t* part, int warmup, int reps,
+                                  double* mean_us_out, double* median_us_out)
+{
+    if (!ctx || !op || reps <= 0 || warmup < 0) return fail(LITHOS_EINVAL, "lithos_time_launch: bad argument");
+    (void)hipSetDevice(ctx->device);
+    OpPlan plan;
+    int rc = op_plan(*op, &plan);
+    if (rc != LITHOS_OK) return rc;
+    if ((rc = check_counters(ctx, plan)) != LITHOS_OK) return rc;
+    hipStream_t s = part ? part->stream : ctx->plain;
+    const int dies = part ? part->n_dies : ctx->n_xcd;
+    const uint32_t total = plan.total;
+    const uint32_t B = (atom_blocks == 0 || atom_blocks >= total) ? total : atom_blocks;
+    hipEvent_t e0, e1;
+    LITHOS_HIP(hipEventCreate(&e0));
+    LITHOS_HIP(hipEventCreate(&e1));
+    std::vector<float> ms(reps);
+    hipError_t e = hipSuccess;
+    for (int r = -warmup; r < reps && rc == LITHOS_OK && e == hipSuccess; ++r) {
+        if (r >= 0) e = hipEventRecord(e0, s);
+        for (uint32_t lo = 0; lo < total && rc == LITHOS_OK; lo += B)
+            rc = op_launch(*op, plan, make_atom(ctx, plan, lo, std::min(lo + B, total), dies), s);
+        if (r >= 0) {
+            if (e == hipSuccess) e = hipEventRecord(e1, s);
+            if (e == hipSuccess) e = hipEventSynchronize(e1);
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms[r], e0, e1);
+        }
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != LITHOS_OK) return rc;
+    if (e != hipSuccess) return fail(LITHOS_EHIP, "lithos_time_launch: %s", hipGetErrorString(e));
+    double sum = 0;
+    for (float v : ms) sum += v;
+    std::sort(ms.begin(), ms.end());
+    if (mean_us_out) *mean_us_out = sum / reps * 1000.0;
+    if (median_us_out) *median_us_out = ((reps & 1) ? ms[reps / 2] : 0.5 * (ms[reps / 2 - 1] + ms[reps / 2])) * 1000.0;
+    return LITHOS_OK;
+}

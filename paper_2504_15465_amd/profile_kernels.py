@@ -1,0 +1,68 @@
+"""Run a named kernel a few times, for use under rocprofv3.
+
+    rocprofv3 --kernel-trace --stats -d OUT -- python3 -m paper_2504_15465_amd.profile_kernels --what gemm8192
+    rocprofv3 --pmc FETCH_SIZE -d OUT -- python3 -m paper_2504_15465_amd.profile_kernels --what gemm8192 --copy-calibration
+
+``--copy-calibration`` first runs a plain device-to-device copy of 1 GiB (torch's
+copy kernel: reads 1 GiB, writes 1 GiB) so that the same counter can be read for
+a kernel whose HBM traffic is known, then the kernel under study.
+"""
+from __future__ import annotations
+
+import argparse
+
+import torch
+
+from . import binding as B
+from . import inputs
+from .models import MlpChain
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "mlp", "skinny"])
+    ap.add_argument("--tile", type=int, default=128)
+    ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--cus", type=int, default=256)
+    ap.add_argument("--copy-calibration", action="store_true")
+    args = ap.parse_args()
+
+    ctx = B.lithos_init(0, None)
+    part = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, args.cus))
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    if args.what.startswith("gemm8192"):
+        n = 8192
+        a_bits, b_bits = inputs.gemm_operands(n, n, n, seed=4)
+        a, b = inputs.bits_to_torch(a_bits, "cuda"), inputs.bits_to_torch(b_bits, "cuda")
+        c = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
+        op = B.gemm_op(a, b, c, n, n, n, tile=args.tile)
+        grid, wg = B.lithos_op_grid(ctx, op)
+        atom = 0 if args.what == "gemm8192" else args.cus * wg
+        torch.cuda.synchronize()
+        for _ in range(args.reps):
+            B.lithos_launch_atomized(ctx, op, (0, 0, 0), atom, part, None)
+        B.lithos_partition_sync(ctx, part)
+    elif args.what in ("mlp", "skinny"):
+        layers = inputs.mlp_params(6, 4096, seed=1)
+        chain = MlpChain(layers, 8)
+        chain.set_input(inputs.mlp_requests(1, 8, 4096, 2)[0])
+        ops = chain.ops()
+        if args.what == "skinny":
+            ops = [o for o in ops if o.kind == B.OP_GEMM]
+        torch.cuda.synchronize()
+        for _ in range(args.reps):
+            for o in ops:
+                B.lithos_launch_atomized(ctx, o, (0, 0, 0), 0, part, None)
+        B.lithos_partition_sync(ctx, part)
+    B.lithos_destroy_partition(part)
+    B.lithos_shutdown(ctx)
+
+
+if __name__ == "__main__":
+    main()
