@@ -61,6 +61,8 @@ enum {
 #define LITHOS_F_RESIDUAL  (1u << 4)   /* add residual[m,n] (fp32) after the activation */
 #define LITHOS_F_OUT_F32   (1u << 5)   /* out[0] is fp32 (default bf16) */
 #define LITHOS_F_IN_F32    (1u << 6)   /* in[0] is fp32 (default bf16) */
+#define LITHOS_F_SPLIT_A   (1u << 7)   /* GEMM: A is a bf16 pair hi + lo (two planes, dim[3] elements apart) */
+#define LITHOS_F_OUT_SPLIT (1u << 8)   /* producer also writes the lo plane: lo = bf16(y - bf16(y)) */
 
 /* GEMM tile selectors for lithos_op_t.tile (0 = library chooses) */
 #define LITHOS_TILE_64     64    /* 64x64 output tile */
@@ -79,11 +81,19 @@ enum {
  * ATTN_ENC    batch,heads,seq,d                  qkv[batch*seq,3*heads*d] / o[batch*seq,heads*d]  fparam0=scale
  * ATTN_DEC    batch,n_q,n_kv,d,keys,cap          q,kcache,vcache / o                  ld0=q row stride; fparam0=scale
  *             caches are [batch,cap,n_kv,d] bf16; the first `keys` positions are read
- * RMSNORM     rows,H                             x(f32),w(f32) / y(bf16)              fparam0=eps
+ * RMSNORM     rows,H                             x,w(f32) / y                         fparam0=eps
  * ROPE_KV     rows,n_q,n_kv,d,pos,cap            qkv[rows,(n_q+2n_kv)d] (in place) / kcache,vcache   fparam0=theta
+ *             qkv is bf16, or fp32 with IN_F32; the caches are always bf16 (rounded on append)
  * SILU_MUL    rows,F                             gu[rows,2F] / y[rows,F]
+ * IN_F32 / OUT_F32 select fp32 for in[0] / out[0] of the row kernels and of ATTN_DEC's q / o;
+ * GEMM takes IN_F32 (fp32 A) only in its M <= 32 weight-streaming form.
  * SPIN        blocks,ticks                       - / -
  *
+ * Split bf16 ("hi + lo"): a tensor stored as two bf16 planes whose sum carries ~16 significant
+ * bits.  GEMM reads A that way with SPLIT_A (MFMA tile kernels, 64 and 128 tiles) and writes C that
+ * way with OUT_SPLIT (lo plane dim[4] elements after C); LAYERNORM with OUT_F32 | OUT_SPLIT writes
+ * the pair to out[1] (lo plane rows*H elements after hi); ATTN_ENC with OUT_SPLIT writes the pair
+ * to out[0] (lo plane batch*seq*heads*d elements after hi).
  * bf16 tensors are row-major with 16-byte aligned rows; K, lda, ldb multiples of 8.
  * LAYERNORM with OUT_F32 may also write a bf16 copy to out[1] (NULL = none).
  */

@@ -95,6 +95,13 @@ def round_bf16(x) -> np.ndarray:
     return out
 
 
+def round_bf16x2(x) -> np.ndarray:
+    """Value of a split-bf16 pair: hi + lo with hi = bf16(x), lo = bf16(x - hi)."""
+    a = np.asarray(x, dtype=np.float64)
+    hi = round_bf16(a)
+    return hi + round_bf16(a - hi)
+
+
 # ------------------------------------------------------------------ GEMM ---
 
 def gemm(a, b_bits, ta: bool = False, tb: bool = False, fast: bool = True) -> np.ndarray:

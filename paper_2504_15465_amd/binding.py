@@ -21,7 +21,7 @@ MASK_WORDS = 8
 MAX_SWEEP = 64
 
 OP_GEMM, OP_BIAS_ACT, OP_LAYERNORM, OP_SOFTMAX, OP_ATTN_ENC, OP_ATTN_DEC, OP_RMSNORM, OP_ROPE_KV, OP_SILU_MUL, OP_SPIN = range(1, 11)
-F_TRANS_A, F_TRANS_B, F_BIAS, F_GELU, F_RESIDUAL, F_OUT_F32, F_IN_F32 = (1 << i for i in range(7))
+F_TRANS_A, F_TRANS_B, F_BIAS, F_GELU, F_RESIDUAL, F_OUT_F32, F_IN_F32, F_SPLIT_A, F_OUT_SPLIT = (1 << i for i in range(9))
 TILE_AUTO, TILE_SKINNY, TILE_64, TILE_128, TILE_256 = 0, 1, 64, 128, 256
 MASK_STRIPED, MASK_WHOLE_XCD = 0, 1
 CLASS_HP, CLASS_BE = 0, 1
@@ -145,7 +145,8 @@ def make_op(kind, dims=(), flags=0, tile=0, ld=(), fparam=(), inputs=(), outputs
 
 
 def gemm_op(a, b, c, m, n, k, ta=False, tb=False, bias=None, gelu=False, residual=None, tile=0,
-            lda=None, ldb=None, ldc=None, ldr=None, op_id=0) -> Op:
+            lda=None, ldb=None, ldc=None, ldr=None, op_id=0, a_split=False, c_split=False) -> Op:
+    """``a_split``: ``a`` is a [2, M, K] bf16 pair (hi, lo planes); ``c_split``: ``c`` is a [2, M, N] pair."""
     flags = (F_TRANS_A if ta else 0) | (F_TRANS_B if tb else 0) | (F_BIAS if bias is not None else 0)
     flags |= (F_GELU if gelu else 0) | (F_RESIDUAL if residual is not None else 0)
     if isinstance(c, torch.Tensor) and c.dtype == torch.float32:
@@ -156,7 +157,9 @@ def gemm_op(a, b, c, m, n, k, ta=False, tb=False, bias=None, gelu=False, residua
     ldb = ldb if ldb is not None else (k if tb else n)
     ldc = ldc if ldc is not None else n
     ldr = ldr if ldr is not None else n
-    return make_op(OP_GEMM, (m, n, k), flags, tile, (lda, ldb, ldc, ldr), (), (a, b, bias, residual), (c,), op_id)
+    flags |= (F_SPLIT_A if a_split else 0) | (F_OUT_SPLIT if c_split else 0)
+    return make_op(OP_GEMM, (m, n, k, m * lda if a_split else 0, m * ldc if c_split else 0), flags, tile,
+                   (lda, ldb, ldc, ldr), (), (a, b, bias, residual), (c,), op_id)
 
 
 def bias_act_op(x, y, rows, cols, bias=None, gelu=True, op_id=0) -> Op:
@@ -166,13 +169,21 @@ def bias_act_op(x, y, rows, cols, bias=None, gelu=True, op_id=0) -> Op:
     return make_op(OP_BIAS_ACT, (rows, cols), flags, inputs=(x, bias), outputs=(y,), op_id=op_id)
 
 
-def layernorm_op(x, gamma, beta, y, rows, h, eps=1e-5, y_bf16=None, op_id=0) -> Op:
+def split_op(x, y_pair, rows, cols, op_id=0) -> Op:
+    """fp32 (or bf16) x -> [2, rows, cols] bf16 pair: hi = bf16(x), lo = bf16(x - hi)."""
+    flags = (F_IN_F32 if x.dtype == torch.float32 else 0) | F_OUT_SPLIT
+    return make_op(OP_BIAS_ACT, (rows, cols), flags, inputs=(x, None), outputs=(y_pair,), op_id=op_id)
+
+
+def layernorm_op(x, gamma, beta, y, rows, h, eps=1e-5, y_bf16=None, op_id=0, split=False) -> Op:
+    """``split``: ``y_bf16`` is a [2, rows, h] bf16 pair (hi, lo planes)."""
     flags = (F_IN_F32 if x.dtype == torch.float32 else 0) | (F_OUT_F32 if y.dtype == torch.float32 else 0)
+    flags |= F_OUT_SPLIT if split else 0
     return make_op(OP_LAYERNORM, (rows, h), flags, fparam=(eps,), inputs=(x, gamma, beta), outputs=(y, y_bf16), op_id=op_id)
 
 
 def rmsnorm_op(x, w, y, rows, h, eps=1e-5, op_id=0) -> Op:
-    flags = F_IN_F32 if x.dtype == torch.float32 else 0
+    flags = (F_IN_F32 if x.dtype == torch.float32 else 0) | (F_OUT_F32 if y.dtype == torch.float32 else 0)
     return make_op(OP_RMSNORM, (rows, h), flags, fparam=(eps,), inputs=(x, w), outputs=(y,), op_id=op_id)
 
 
@@ -182,20 +193,25 @@ def softmax_op(s, p, rows, n, scale=1.0, op_id=0) -> Op:
 
 
 def silu_mul_op(gu, y, rows, f, op_id=0) -> Op:
-    return make_op(OP_SILU_MUL, (rows, f), inputs=(gu,), outputs=(y,), op_id=op_id)
+    flags = (F_IN_F32 if gu.dtype == torch.float32 else 0) | (F_OUT_F32 if y.dtype == torch.float32 else 0)
+    return make_op(OP_SILU_MUL, (rows, f), flags, inputs=(gu,), outputs=(y,), op_id=op_id)
 
 
 def rope_kv_op(qkv, kcache, vcache, rows, n_q, n_kv, d, pos, cap, theta=10000.0, op_id=0) -> Op:
-    return make_op(OP_ROPE_KV, (rows, n_q, n_kv, d, pos, cap), fparam=(theta,), inputs=(qkv,),
+    flags = F_IN_F32 if qkv.dtype == torch.float32 else 0
+    return make_op(OP_ROPE_KV, (rows, n_q, n_kv, d, pos, cap), flags, fparam=(theta,), inputs=(qkv,),
                    outputs=(kcache, vcache), op_id=op_id)
 
 
-def attn_enc_op(qkv, o, batch, heads, seq, d, scale, op_id=0) -> Op:
-    return make_op(OP_ATTN_ENC, (batch, heads, seq, d), fparam=(scale,), inputs=(qkv,), outputs=(o,), op_id=op_id)
+def attn_enc_op(qkv, o, batch, heads, seq, d, scale, op_id=0, split=False) -> Op:
+    """``split``: ``o`` is a [2, batch*seq, heads*d] bf16 pair (hi, lo planes)."""
+    return make_op(OP_ATTN_ENC, (batch, heads, seq, d), F_OUT_SPLIT if split else 0, fparam=(scale,),
+                   inputs=(qkv,), outputs=(o,), op_id=op_id)
 
 
 def attn_dec_op(q, kcache, vcache, o, batch, n_q, n_kv, d, keys, cap, scale, ldq=None, op_id=0) -> Op:
-    return make_op(OP_ATTN_DEC, (batch, n_q, n_kv, d, keys, cap), ld=(ldq if ldq is not None else n_q * d,),
+    flags = (F_IN_F32 if q.dtype == torch.float32 else 0) | (F_OUT_F32 if o.dtype == torch.float32 else 0)
+    return make_op(OP_ATTN_DEC, (batch, n_q, n_kv, d, keys, cap), flags, ld=(ldq if ldq is not None else n_q * d,),
                    fparam=(scale,), inputs=(q, kcache, vcache), outputs=(o,), op_id=op_id)
 
 

@@ -1,6 +1,347 @@
-// placeholder replaced below
+// Atom-aware attention kernels for gfx950.
+//
+//  * attn_enc_kernel - full (unmasked) multi-head attention on a packed
+//    [tokens, 3*heads*d] bf16 qkv tensor, d = 64, sequence 64/128/256.  One
+//    workgroup per (batch, head); each of its wavefronts owns 32 queries and
+//    runs both products on MFMA (v_mfma_f32_32x32x16_bf16):
+//      S^T = K Q^T   (keys x queries: a lane then holds ONE query's scores, so
+//                     the softmax needs a single cross-lane step)
+//      O^T = V^T P^T (P^T is fed to the MFMA straight from the accumulator
+//                     registers; only V is transposed, through LDS)
+//  * attn_dec_kernel - one query token per sequence against a bf16 key/value
+//    cache with grouped-query sharing (HBM-bound: the cache is streamed once).
+//    One workgroup per (sequence, key/value head); its wavefronts split the
+//    keys, each handling all query heads of the group with an online softmax;
+//    the partial results are merged in a fixed order.
+//
+// Every workgroup works on the (batch, head) named by its LOGICAL block index
+// (LithOS Section 4.4), so any sub-range of blocks is a valid atom.
 #include "common.hpp"
+#include <math.h>
+
 namespace lithos {
-int attn_plan(const lithos_op_t& op, OpPlan*) { return fail(LITHOS_EINVAL, "attention kind %d is not built", op.kind); }
-int attn_launch(const lithos_op_t& op, const OpPlan&, const AtomArgs&, hipStream_t) { return fail(LITHOS_EINVAL, "attention kind %d is not built", op.kind); }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct AttnArgs {
+    const void* q;          // enc: packed qkv (bf16); dec: q rows (bf16 or fp32)
+    const uint16_t* k;      // dec: key cache
+    const uint16_t* v;      // dec: value cache
+    void* o;
+    int batch, n_q, n_kv, d, seq, cap;
+    int64_t ldq;
+    float scale;
+    uint32_t flags;
+};
+
+__device__ __forceinline__ uint16_t attn_f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
 }
+
+__device__ __forceinline__ float attn_bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// ---- encoder -------------------------------------------------------------------
+// NKB = seq / 32 key blocks, D = 64.  4 wavefronts when seq >= 128, else seq/32.
+template <int NKB>
+__global__ __launch_bounds__(256) void attn_enc_kernel(AttnArgs a, AtomArgs atom)
+{
+    constexpr int D = 64, SEQ = NKB * 32, VT_LD = SEQ + 4;       // padded V^T rows
+    constexpr int WAVES = 4;
+    __shared__ __attribute__((aligned(16))) uint16_t vt[D * VT_LD];
+
+    const uint32_t L = atom_logical_block(atom);
+    const int b = L / a.n_q, h = L % a.n_q;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int64_t row_stride = 3 * (int64_t)a.n_q * D;           // elements per token
+    const uint16_t* base = reinterpret_cast<const uint16_t*>(a.q) + (int64_t)b * SEQ * row_stride + h * D;
+    const uint16_t* qp = base;
+    const uint16_t* kp = base + (int64_t)a.n_q * D;
+    const uint16_t* vp = base + 2 * (int64_t)a.n_q * D;
+
+    // V -> LDS, transposed: vt[d][key]
+    for (int c = tid; c < SEQ * D / 8; c += 256) {
+        int key = c >> 3, d0 = (c & 7) * 8;
+        uint4 v = *reinterpret_cast<const uint4*>(vp + key * row_stride + d0);
+        uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vt[(d0 + j) * VT_LD + key] = (uint16_t)(u[j >> 1] >> ((j & 1) * 16));
+    }
+    __syncthreads();
+
+    // Sequences longer than 128 give a wavefront several 32-query groups.
+    for (int qg = wave; qg < NKB; qg += WAVES) {
+        const int q0 = qg * 32;
+        // S^T[key][query] = sum_d K[key][d] Q[query][d]
+        f32x16 s[NKB];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[kb][e] = 0.0f;
+#pragma unroll
+        for (int ds = 0; ds < D / 16; ++ds) {
+            const int d0 = ds * 16 + half * 8;
+            bf16x8 qf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + (q0 + l32) * row_stride + d0));
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kp + (kb * 32 + l32) * row_stride + d0));
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, s[kb], 0, 0, 0);
+            }
+        }
+        // softmax over keys for this lane's query (the other half-wave holds the other keys)
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { s[kb][e] *= a.scale; mx = fmaxf(mx, s[kb][e]); }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        float sum = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { s[kb][e] = expf(s[kb][e] - mx); sum += s[kb][e]; }
+        sum += __shfl_xor(sum, 32, 64);
+        const float inv = 1.0f / sum;
+
+        // O^T[d][query] = sum_key V^T[d][key] P^T[key][query]
+        // accumulator element e of block kb is key 32 kb + 8 (e/4) + 4 half + e%4, so
+        // MFMA k-slot j of step (kb, gp) is key 32 kb + 16 gp + 8 (j/4) + 4 half + j%4
+        // = accumulator element 8 gp + j: eight consecutive registers.
+        f32x16 o[D / 32];
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int gp = 0; gp < 2; ++gp) {
+                uint32_t pw[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    uint32_t lo = attn_f32_to_bf16(s[kb][8 * gp + 2 * p] * inv);
+                    uint32_t hi = attn_f32_to_bf16(s[kb][8 * gp + 2 * p + 1] * inv);
+                    pw[p] = lo | (hi << 16);
+                }
+                bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+                const int key0 = kb * 32 + gp * 16 + half * 4;
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db) {
+                    const uint16_t* vrow = vt + (db * 32 + l32) * VT_LD + key0;
+                    uint2 v0 = *reinterpret_cast<const uint2*>(vrow);
+                    uint2 v1 = *reinterpret_cast<const uint2*>(vrow + 8);
+                    bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(v0.x, v0.y, v1.x, v1.y));
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[db], 0, 0, 0);
+                }
+            }
+        // o[db][e] is d = 32 db + 8 (e/4) + 4 half + e%4 of query q0 + l32
+        uint16_t* op = reinterpret_cast<uint16_t*>(a.o) + ((int64_t)b * SEQ + q0 + l32) * ((int64_t)a.n_q * D) + h * D;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint16_t hi[4], lo[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    hi[e] = attn_f32_to_bf16(o[db][4 * g + e]);
+                    lo[e] = attn_f32_to_bf16(o[db][4 * g + e] - attn_bf16_to_f32(hi[e]));
+                }
+                *reinterpret_cast<uint2*>(op + db * 32 + 8 * g + 4 * half) =
+                    make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+                if (a.flags & LITHOS_F_OUT_SPLIT)
+                    *reinterpret_cast<uint2*>(op + (int64_t)a.batch * SEQ * a.n_q * D + db * 32 + 8 * g + 4 * half) =
+                        make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+            }
+    }
+}
+
+// ---- decode, grouped-query -------------------------------------------------------
+// G = query heads per key/value head (1, 2 or 4), D = 128.
+// Phase per 64-key batch of a wavefront: lane = key for the scores (q is read
+// from LDS with broadcast reads), lane = d-pair for the value sum (probabilities
+// are broadcast with readlane).
+template <int G, bool Q32, bool O32>
+__global__ __launch_bounds__(256) void attn_dec_kernel(AttnArgs a, AtomArgs atom)
+{
+    constexpr int D = 128;
+    __shared__ __attribute__((aligned(16))) float qs[G * D];
+    __shared__ float part_m[4][G], part_l[4][G];
+    __shared__ __attribute__((aligned(16))) float part_o[4][G][D];
+
+    const uint32_t L = atom_logical_block(atom);
+    const int b = L / a.n_kv, g = L % a.n_kv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    for (int i = tid; i < G * D; i += 256) {
+        int64_t idx = (int64_t)b * a.ldq + (g * G) * D + i;
+        float v;
+        if constexpr (Q32) v = reinterpret_cast<const float*>(a.q)[idx];
+        else v = attn_bf16_to_f32(reinterpret_cast<const uint16_t*>(a.q)[idx]);
+        qs[i] = v * a.scale;
+    }
+    __syncthreads();
+
+    const int64_t tok_stride = (int64_t)a.n_kv * D;
+    const uint16_t* kbase = a.k + ((int64_t)b * a.cap * a.n_kv + g) * D;
+    const uint16_t* vbase = a.v + ((int64_t)b * a.cap * a.n_kv + g) * D;
+    const int T = a.seq;
+
+    float m[G], l[G], acc[G][2];
+#pragma unroll
+    for (int h = 0; h < G; ++h) { m[h] = -INFINITY; l[h] = 0.0f; acc[h][0] = acc[h][1] = 0.0f; }
+
+    for (int t0 = wave * 64; t0 < T; t0 += 256) {
+        const int t = t0 + lane;
+        const bool live = t < T;
+        float sc[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) sc[h] = 0.0f;
+        const uint16_t* krow = kbase + (int64_t)(live ? t : T - 1) * tok_stride;
+#pragma unroll
+        for (int c = 0; c < D / 8; ++c) {
+            uint4 kv = *reinterpret_cast<const uint4*>(krow + c * 8);
+            uint32_t u[4] = {kv.x, kv.y, kv.z, kv.w};
+            float kf[8];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) { kf[2 * p] = __uint_as_float(u[p] << 16); kf[2 * p + 1] = __uint_as_float(u[p] & 0xffff0000u); }
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float4 q0 = *reinterpret_cast<const float4*>(qs + h * D + c * 8);
+                const float4 q1 = *reinterpret_cast<const float4*>(qs + h * D + c * 8 + 4);
+                sc[h] += kf[0] * q0.x + kf[1] * q0.y + kf[2] * q0.z + kf[3] * q0.w
+                       + kf[4] * q1.x + kf[5] * q1.y + kf[6] * q1.z + kf[7] * q1.w;
+            }
+        }
+        float p[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float s = live ? sc[h] : -INFINITY;
+            float bm = s;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) bm = fmaxf(bm, __shfl_xor(bm, off, 64));
+            const float nm = fmaxf(m[h], bm);
+            const float corr = expf(m[h] - nm);           // 0 on the first batch (m = -inf)
+            p[h] = live ? expf(s - nm) : 0.0f;
+            float bs = p[h];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) bs += __shfl_xor(bs, off, 64);
+            l[h] = l[h] * corr + bs;
+            acc[h][0] *= corr; acc[h][1] *= corr;
+            m[h] = nm;
+        }
+        // value sum: lane owns d = 2*lane, 2*lane+1
+        const int nkeys = min(64, T - t0);
+        for (int j = 0; j < nkeys; ++j) {
+            const uint32_t vv = *reinterpret_cast<const uint32_t*>(vbase + (int64_t)(t0 + j) * tok_stride + 2 * lane);
+            const float v0 = __uint_as_float(vv << 16), v1 = __uint_as_float(vv & 0xffff0000u);
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float pj = __shfl(p[h], j, 64);
+                acc[h][0] += pj * v0;
+                acc[h][1] += pj * v1;
+            }
+        }
+    }
+
+    // merge the four wavefronts' partial softmaxes in wave order
+    if (lane == 0)
+#pragma unroll
+        for (int h = 0; h < G; ++h) { part_m[wave][h] = m[h]; part_l[wave][h] = l[h]; }
+#pragma unroll
+    for (int h = 0; h < G; ++h) { part_o[wave][h][2 * lane] = acc[h][0]; part_o[wave][h][2 * lane + 1] = acc[h][1]; }
+    __syncthreads();
+    for (int i = tid; i < G * D; i += 256) {
+        const int h = i / D, d = i % D;
+        float gm = -INFINITY;
+        for (int w = 0; w < 4; ++w) gm = fmaxf(gm, part_m[w][h]);
+        float num = 0.0f, den = 0.0f;
+        for (int w = 0; w < 4; ++w) {
+            const float f = expf(part_m[w][h] - gm);      // 0 for a wavefront that saw no key
+            num += part_o[w][h][d] * f;
+            den += part_l[w][h] * f;
+        }
+        const float r = num / den;
+        const int64_t idx = (int64_t)b * ((int64_t)a.n_q * D) + (g * G + h) * D + d;
+        if constexpr (O32) reinterpret_cast<float*>(a.o)[idx] = r;
+        else reinterpret_cast<uint16_t*>(a.o)[idx] = attn_f32_to_bf16(r);
+    }
+}
+
+// ---- host side ----------------------------------------------------------------------
+
+typedef void (*attn_fn)(AttnArgs, AtomArgs);
+
+static attn_fn dec_fn(int G, bool q32, bool o32)
+{
+#define PICKG(GG) (q32 ? (o32 ? (attn_fn)attn_dec_kernel<GG, true, true> : (attn_fn)attn_dec_kernel<GG, true, false>) \
+                       : (o32 ? (attn_fn)attn_dec_kernel<GG, false, true> : (attn_fn)attn_dec_kernel<GG, false, false>))
+    switch (G) {
+    case 1: return PICKG(1);
+    case 2: return PICKG(2);
+    default: return PICKG(4);
+    }
+#undef PICKG
+}
+
+int attn_plan(const lithos_op_t& op, OpPlan* plan)
+{
+    plan->threads = 256;
+    plan->variant = 0;
+    if (op.kind == LITHOS_OP_ATTN_ENC) {
+        const int64_t batch = op.dim[0], heads = op.dim[1], seq = op.dim[2], d = op.dim[3];
+        if (batch <= 0 || heads <= 0 || batch * heads > 0x7fffffff) return fail(LITHOS_EINVAL, "attn_enc: batch and heads must be positive");
+        if (d != 64) return fail(LITHOS_EINVAL, "attn_enc: head width %lld is not built (64 only)", (long long)d);
+        if (seq != 64 && seq != 128 && seq != 256) return fail(LITHOS_EINVAL, "attn_enc: sequence length %lld is not built (64, 128, 256)", (long long)seq);
+        if (!op.in[0] || !op.out[0] || !aligned16(op.in[0]) || (reinterpret_cast<uintptr_t>(op.out[0]) & 7u))
+            return fail(LITHOS_EINVAL, "attn_enc: null or misaligned qkv / output");
+        plan->grid = {(uint32_t)heads, (uint32_t)batch, 1};
+        plan->total = (uint32_t)(batch * heads);
+        plan->wg_per_cu = 2;
+        return LITHOS_OK;
+    }
+    // decode: dim = batch, n_q, n_kv, d, keys, cap
+    const int64_t batch = op.dim[0], n_q = op.dim[1], n_kv = op.dim[2], d = op.dim[3], keys = op.dim[4], cap = op.dim[5];
+    if (batch <= 0 || n_q <= 0 || n_kv <= 0 || n_q % n_kv) return fail(LITHOS_EINVAL, "attn_dec: need batch > 0 and n_kv dividing n_q");
+    const int64_t G = n_q / n_kv;
+    if (G != 1 && G != 2 && G != 4) return fail(LITHOS_EINVAL, "attn_dec: group size %lld is not built (1, 2, 4)", (long long)G);
+    if (d != 128) return fail(LITHOS_EINVAL, "attn_dec: head width %lld is not built (128 only)", (long long)d);
+    if (keys <= 0 || keys > cap) return fail(LITHOS_EINVAL, "attn_dec: need 0 < keys <= cap");
+    if (op.ld[0] < n_q * d) return fail(LITHOS_EINVAL, "attn_dec: q row stride smaller than n_q*d");
+    if (!op.in[0] || !op.in[1] || !op.in[2] || !op.out[0]) return fail(LITHOS_EINVAL, "attn_dec: null operand");
+    if (!aligned16(op.in[1]) || !aligned16(op.in[2])) return fail(LITHOS_EINVAL, "attn_dec: caches must be 16-byte aligned");
+    plan->grid = {(uint32_t)n_kv, (uint32_t)batch, 1};
+    plan->total = (uint32_t)(batch * n_kv);
+    plan->wg_per_cu = 4;
+    return LITHOS_OK;
+}
+
+int attn_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, hipStream_t s)
+{
+    AttnArgs a{};
+    a.q = op.in[0];
+    a.o = op.out[0];
+    a.scale = op.fparam[0];
+    a.flags = op.flags;
+    const dim3 grid(atom.n), block(256);
+    if (op.kind == LITHOS_OP_ATTN_ENC) {
+        a.batch = (int)op.dim[0]; a.n_q = (int)op.dim[1]; a.seq = (int)op.dim[2]; a.d = (int)op.dim[3];
+        attn_fn fn = a.seq == 64 ? (attn_fn)attn_enc_kernel<2> : a.seq == 128 ? (attn_fn)attn_enc_kernel<4> : (attn_fn)attn_enc_kernel<8>;
+        LITHOS_HIP(launch_kernel(fn, grid, block, s, a, atom));
+        return LITHOS_OK;
+    }
+    a.k = (const uint16_t*)op.in[1];
+    a.v = (const uint16_t*)op.in[2];
+    a.batch = (int)op.dim[0]; a.n_q = (int)op.dim[1]; a.n_kv = (int)op.dim[2]; a.d = (int)op.dim[3];
+    a.seq = (int)op.dim[4]; a.cap = (int)op.dim[5];
+    a.ldq = op.ld[0];
+    attn_fn fn = dec_fn(a.n_q / a.n_kv, op.flags & LITHOS_F_IN_F32, op.flags & LITHOS_F_OUT_F32);
+    LITHOS_HIP(launch_kernel(fn, grid, block, s, a, atom));
+    return LITHOS_OK;
+}
+
+} // namespace lithos

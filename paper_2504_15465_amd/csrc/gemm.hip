@@ -30,6 +30,8 @@ struct GemmArgs {
     int64_t lda, ldb, ldc, ldr;
     uint32_t flags;
     uint32_t tiles_m, tiles_n;
+    int64_t a_plane;     // SPLIT_A: elements between the hi and the lo plane of A
+    int64_t c_plane;     // OUT_SPLIT: elements between the hi and the lo plane of C
 };
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
@@ -51,10 +53,15 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& g, int m, int n, 
     if (g.flags & LITHOS_F_BIAS) v += g.bias[n];
     if (g.flags & LITHOS_F_GELU) v = gelu_erf(v);
     if (g.flags & LITHOS_F_RESIDUAL) v += g.resid[(int64_t)m * g.ldr + n];
-    if (g.flags & LITHOS_F_OUT_F32)
+    if (g.flags & LITHOS_F_OUT_F32) {
         reinterpret_cast<float*>(g.C)[(int64_t)m * g.ldc + n] = v;
-    else
-        reinterpret_cast<uint16_t*>(g.C)[(int64_t)m * g.ldc + n] = f32_to_bf16_rne(v);
+    } else {
+        uint16_t hi = f32_to_bf16_rne(v);
+        reinterpret_cast<uint16_t*>(g.C)[(int64_t)m * g.ldc + n] = hi;
+        if (g.flags & LITHOS_F_OUT_SPLIT)       // second bf16 carries what the first one dropped
+            reinterpret_cast<uint16_t*>(g.C)[g.c_plane + (int64_t)m * g.ldc + n] =
+                f32_to_bf16_rne(v - __uint_as_float((uint32_t)hi << 16));
+    }
 }
 
 // LDS tiles are [rows][64] bf16 (128-byte rows of eight 16-byte chunks).
@@ -165,13 +172,16 @@ __device__ __forceinline__ void tile_of_block(uint32_t lin, uint32_t tiles_m, ui
     tn = rem / gm;
 }
 
-template <int BM, int BN, bool TA, bool TB>
+// SPLIT: A is a pair of bf16 planes (hi, lo) whose sum carries ~16 significant
+// bits of the activation; both planes are multiplied with the same B operand.
+template <int BM, int BN, bool TA, bool TB, bool SPLIT>
 __global__ __launch_bounds__(256)
 void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 {
     constexpr int T = 256, BK = 64, WGM = 2, WGN = 2;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     __shared__ __attribute__((aligned(16))) uint16_t As[BM * BK];
+    __shared__ __attribute__((aligned(16))) uint16_t As2[SPLIT ? BM * BK : 8];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * BK];
 
     const uint32_t L = atom_logical_block(atom);
@@ -191,28 +201,34 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     TileStage<BM, T, TA> sa;        // A is k-strided in memory when transposed
+    TileStage<SPLIT ? BM : T / 8, T, TA && SPLIT> sa2;   // lo plane of A (a dummy 32-row stage when unused)
     TileStage<BN, T, !TB> sb;       // B is k-strided in memory when NOT transposed
 
     const int KT = (g.K + BK - 1) / BK;
     sa.load(g.A, g.lda, m0, g.M, 0, g.K, tid);
+    if constexpr (SPLIT) sa2.load(g.A + g.a_plane, g.lda, m0, g.M, 0, g.K, tid);
     sb.load(g.B, g.ldb, n0, g.N, 0, g.K, tid);
     sa.store(As, tid);
+    if constexpr (SPLIT) sa2.store(As2, tid);
     sb.store(Bs, tid);
     __syncthreads();
 
     for (int kt = 0; kt < KT; ++kt) {
         if (kt + 1 < KT) {          // next tile's global loads fly during the MFMAs
             sa.load(g.A, g.lda, m0, g.M, (kt + 1) * BK, g.K, tid);
+            if constexpr (SPLIT) sa2.load(g.A + g.a_plane, g.lda, m0, g.M, (kt + 1) * BK, g.K, tid);
             sb.load(g.B, g.ldb, n0, g.N, (kt + 1) * BK, g.K, tid);
         }
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             const int kc = kk * 2 + (lane >> 5);
-            bf16x8 af[MI], bfr[NI];
+            bf16x8 af[MI], af2[MI], bfr[NI];
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
                 int row = wm * WM + i * 32 + (lane & 31);
                 af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(As + lds_index(row, kc)));
+                if constexpr (SPLIT)
+                    af2[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(As2 + lds_index(row, kc)));
             }
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
@@ -222,12 +238,16 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < NI; ++j)
+                for (int j = 0; j < NI; ++j) {
+                    if constexpr (SPLIT)    // small term first
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af2[i], bfr[j], acc[i][j], 0, 0, 0);
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                }
         }
         __syncthreads();            // every wave is done reading this tile
         if (kt + 1 < KT) {
             sa.store(As, tid);
+            if constexpr (SPLIT) sa2.store(As2, tid);
             sb.store(Bs, tid);
             __syncthreads();
         }
@@ -400,30 +420,35 @@ enum { V_SKINNY8 = 1, V_SKINNY16 = 2, V_SKINNY32 = 3, V_TILE64 = 10, V_TILE128 =
 
 typedef void (*gemm_fn)(GemmArgs, AtomArgs);
 
-static gemm_fn tile_fn(int tile, bool ta, bool tb)
+static gemm_fn tile_fn(int tile, bool ta, bool tb, bool split)
 {
-#define PICK(BMN)                                                                   \
-    (ta ? (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, true, true>                     \
-              : (gemm_fn)gemm_tile_kernel<BMN, BMN, true, false>)                   \
-        : (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, false, true>                    \
-              : (gemm_fn)gemm_tile_kernel<BMN, BMN, false, false>))
+#define PICK(BMN)                                                                          \
+    (ta ? (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, true, true, false>                     \
+              : (gemm_fn)gemm_tile_kernel<BMN, BMN, true, false, false>)                   \
+        : (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, false, true, false>                    \
+              : (gemm_fn)gemm_tile_kernel<BMN, BMN, false, false, false>))
+#define PICKS(BMN)                                                                         \
+    (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, false, true, true>                           \
+        : (gemm_fn)gemm_tile_kernel<BMN, BMN, false, false, true>)
+    if (split) return tile == 64 ? PICKS(64) : PICKS(128);
     switch (tile) {
     case 64: return PICK(64);
     case 128: return PICK(128);
     default: return PICK(256);
     }
 #undef PICK
+#undef PICKS
 }
 
-static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32)
+static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split)
 {
     switch (variant) {
     case V_SKINNY8: return a32 ? (gemm_fn)gemm_skinny_kernel<8, true> : (gemm_fn)gemm_skinny_kernel<8, false>;
     case V_SKINNY16: return a32 ? (gemm_fn)gemm_skinny_kernel<16, true> : (gemm_fn)gemm_skinny_kernel<16, false>;
     case V_SKINNY32: return a32 ? (gemm_fn)gemm_skinny_kernel<32, true> : (gemm_fn)gemm_skinny_kernel<32, false>;
-    case V_TILE64: return tile_fn(64, ta, tb);
-    case V_TILE128: return tile_fn(128, ta, tb);
-    default: return tile_fn(256, ta, tb);
+    case V_TILE64: return tile_fn(64, ta, tb, split);
+    case V_TILE128: return tile_fn(128, ta, tb, split);
+    default: return tile_fn(256, ta, tb, split);
     }
 }
 
@@ -431,6 +456,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
 {
     const int64_t M = op.dim[0], N = op.dim[1], K = op.dim[2];
     const bool ta = op.flags & LITHOS_F_TRANS_A, tb = op.flags & LITHOS_F_TRANS_B, a32 = op.flags & LITHOS_F_IN_F32;
+    const bool split = op.flags & LITHOS_F_SPLIT_A, out_split = op.flags & LITHOS_F_OUT_SPLIT;
     if (M <= 0 || N <= 0 || K <= 0 || M > (1 << 30) || N > (1 << 30) || K > (1 << 30))
         return fail(LITHOS_EINVAL, "gemm: M,N,K must be positive (got %lld,%lld,%lld)", (long long)M, (long long)N, (long long)K);
     if (K % 8) return fail(LITHOS_EINVAL, "gemm: K must be a multiple of 8 (got %lld)", (long long)K);
@@ -447,22 +473,28 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         if (!op.in[3]) return fail(LITHOS_EINVAL, "gemm: RESIDUAL set but in[3] is null");
         if (ldr < N) return fail(LITHOS_EINVAL, "gemm: ldr smaller than N");
     }
+    if (split && (ta || a32 || op.dim[3] <= 0 || op.dim[3] % 8))
+        return fail(LITHOS_EINVAL, "gemm: SPLIT_A needs bf16 A, no TRANS_A and a plane stride (dim[3]) that is a positive multiple of 8");
+    if (out_split && ((op.flags & LITHOS_F_OUT_F32) || op.dim[4] <= 0))
+        return fail(LITHOS_EINVAL, "gemm: OUT_SPLIT needs a bf16 output and a positive plane stride (dim[4])");
     int tile = op.tile;
     if (a32 && !(M <= 32 && tb && !ta && (tile == 0 || tile == LITHOS_TILE_SKINNY)))
         return fail(LITHOS_EINVAL, "gemm: fp32 activations (IN_F32) are only taken by the skinny kernel (M <= 32, TRANS_B)");
     if (tile == 0) {
         if (M <= 32 && tb && !ta) tile = LITHOS_TILE_SKINNY;
-        else if (((M + 255) / 256) * ((N + 255) / 256) >= 256) tile = 256;
+        else if (!split && ((M + 255) / 256) * ((N + 255) / 256) >= 256) tile = 256;
         else if (((M + 127) / 128) * ((N + 127) / 128) >= 128) tile = 128;
         else tile = 64;
     }
     int variant;
     if (tile == LITHOS_TILE_SKINNY) {
+        if (split) return fail(LITHOS_EINVAL, "gemm: the skinny kernel takes fp32 activations instead of SPLIT_A");
         if (M > 32 || !tb || ta) return fail(LITHOS_EINVAL, "gemm: the skinny kernel needs M <= 32, TRANS_B and no TRANS_A");
         if (a32 && (lda % 4)) return fail(LITHOS_EINVAL, "gemm: fp32 activations need lda %% 4 == 0");
         variant = M <= 8 ? V_SKINNY8 : M <= 16 ? V_SKINNY16 : V_SKINNY32;
         plan->grid = {(uint32_t)((N + 15) / 16), 1, 1};
     } else if (tile == 64 || tile == 128 || tile == 256) {
+        if (split && tile == 256) return fail(LITHOS_EINVAL, "gemm: SPLIT_A is built for the 64 and 128 tiles only");
         variant = tile == 64 ? V_TILE64 : tile == 128 ? V_TILE128 : V_TILE256;
         plan->grid = {(uint32_t)((N + tile - 1) / tile), (uint32_t)((M + tile - 1) / tile), 1};
     } else {
@@ -472,7 +504,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
     plan->threads = 256;
     plan->variant = variant;
     int occ = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void*)variant_fn(variant, ta, tb, a32), 256, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void*)variant_fn(variant, ta, tb, a32, split), 256, 0);
     plan->wg_per_cu = (e == hipSuccess && occ > 0) ? (uint32_t)occ : 1u;
     if (e != hipSuccess) (void)hipGetLastError();
     return LITHOS_OK;
@@ -490,7 +522,9 @@ int gemm_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     g.lda = op.ld[0]; g.ldb = op.ld[1]; g.ldc = op.ld[2]; g.ldr = op.ld[3];
     g.flags = op.flags;
     g.tiles_m = plan.grid.y; g.tiles_n = plan.grid.x;
-    gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B, op.flags & LITHOS_F_IN_F32);
+    g.a_plane = op.dim[3]; g.c_plane = op.dim[4];
+    gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B, op.flags & LITHOS_F_IN_F32,
+                            op.flags & LITHOS_F_SPLIT_A);
     LITHOS_HIP(launch_kernel(fn, dim3(atom.n), dim3(256), s, g, atom));
     return LITHOS_OK;
 }

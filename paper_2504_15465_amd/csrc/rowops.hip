@@ -109,26 +109,30 @@ __global__ __launch_bounds__(256) void bias_act_kernel(RowArgs a, AtomArgs atom)
             if (a.flags & LITHOS_F_BIAS) v += a.p0[idx % a.cols];
             if (a.flags & LITHOS_F_GELU) v = gelu_erf_f(v);
             store_elem<OUT32>(a.y, idx, v);
+            if (!OUT32 && (a.flags & LITHOS_F_OUT_SPLIT)) {      // lo plane follows the hi plane
+                float hi = bf16_bits_to_f32(f32_to_bf16_bits(v));
+                reinterpret_cast<uint16_t*>(a.y)[total + idx] = f32_to_bf16_bits(v - hi);
+            }
         }
     }
 }
 
 // ---- y[r, :F] = silu(gu[r, :F]) * gu[r, F:2F] ------------------------------
+template <bool IN32, bool OUT32>
 __global__ __launch_bounds__(256) void silu_mul_kernel(RowArgs a, AtomArgs atom)
 {
     const uint32_t L = atom_logical_block(atom);
     const int64_t F = a.cols, total = a.rows * F;
     const int64_t base = (int64_t)L * 2048;
-    const uint16_t* gu = reinterpret_cast<const uint16_t*>(a.x);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         int64_t idx = base + threadIdx.x + i * 256;
         if (idx < total) {
             int64_t r = idx / F, c = idx % F;
-            float g = bf16_bits_to_f32(gu[r * 2 * F + c]);
-            float u = bf16_bits_to_f32(gu[r * 2 * F + F + c]);
+            float g = load_elem<IN32>(a.x, r * 2 * F + c);
+            float u = load_elem<IN32>(a.x, r * 2 * F + F + c);
             float v = g / (1.0f + expf(-g)) * u;
-            reinterpret_cast<uint16_t*>(a.y)[idx] = f32_to_bf16_bits(v);
+            store_elem<OUT32>(a.y, idx, v);
         }
     }
 }
@@ -154,12 +158,17 @@ __global__ __launch_bounds__(256) void layernorm_kernel(RowArgs a, AtomArgs atom
     if (live) for (int64_t c = t; c < H; c += TPR) {
         float v = (load_elem<IN32>(a.x, off + c) - mean) * rstd * a.p0[c] + a.p1[c];
         store_elem<OUT32>(a.y, off + c, v);
-        if (OUT32 && a.y2) reinterpret_cast<uint16_t*>(a.y2)[off + c] = f32_to_bf16_bits(v);
+        if (OUT32 && a.y2) {
+            uint16_t hi = f32_to_bf16_bits(v);
+            reinterpret_cast<uint16_t*>(a.y2)[off + c] = hi;
+            if (a.flags & LITHOS_F_OUT_SPLIT)
+                reinterpret_cast<uint16_t*>(a.y2)[a.rows * H + off + c] = f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
+        }
     }
 }
 
 // ---- RMSNorm ----------------------------------------------------------------
-template <bool IN32, int TPR>
+template <bool IN32, bool OUT32, int TPR>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(RowArgs a, AtomArgs atom)
 {
     __shared__ float red[4];
@@ -174,7 +183,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(RowArgs a, AtomArgs atom)
     const float ms = row_sum<TPR>(s, red) / (float)H;
     const float rinv = 1.0f / sqrtf(ms + a.f0);
     if (live) for (int64_t c = t; c < H; c += TPR)
-        reinterpret_cast<uint16_t*>(a.y)[off + c] = f32_to_bf16_bits(load_elem<IN32>(a.x, off + c) * rinv * a.p0[c]);
+        store_elem<OUT32>(a.y, off + c, load_elem<IN32>(a.x, off + c) * rinv * a.p0[c]);
 }
 
 // ---- softmax(scale * s) -----------------------------------------------------
@@ -202,6 +211,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(RowArgs a, AtomArgs atom)
 // One wavefront per (row, head slot); slots 0..n_q-1 are query heads,
 // n_q..n_q+n_kv-1 key heads, the rest value heads (copied to the cache only).
 // aux = {n_q, n_kv, pos, cap}; cols = d.
+template <bool F32>
 __global__ __launch_bounds__(256) void rope_kv_kernel(RowArgs a, AtomArgs atom)
 {
     const uint32_t L = atom_logical_block(atom);
@@ -211,7 +221,8 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RowArgs a, AtomArgs atom)
     if (unit >= a.rows * slots) return;
     const int lane = threadIdx.x & 63;
     const int64_t row = unit / slots, slot = unit % slots;
-    uint16_t* head = reinterpret_cast<uint16_t*>(const_cast<void*>(a.x)) + row * slots * d + slot * d;
+    void* head = const_cast<void*>(a.x);
+    const int64_t hoff = row * slots * d + slot * d;
     uint16_t* kc = reinterpret_cast<uint16_t*>(a.y);
     uint16_t* vc = reinterpret_cast<uint16_t*>(a.y2);
     const int64_t half = d / 2;
@@ -222,15 +233,15 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RowArgs a, AtomArgs atom)
             float inv = powf(a.f0, -2.0f * (float)e / (float)d);
             float sn, cs;
             sincosf((float)pos * inv, &sn, &cs);
-            float x0 = bf16_bits_to_f32(head[e]), x1 = bf16_bits_to_f32(head[e + half]);
-            uint16_t y0 = f32_to_bf16_bits(x0 * cs - x1 * sn);
-            uint16_t y1 = f32_to_bf16_bits(x1 * cs + x0 * sn);
-            head[e] = y0; head[e + half] = y1;
-            if (dst) { dst[e] = y0; dst[e + half] = y1; }
+            float x0 = load_elem<F32>(head, hoff + e), x1 = load_elem<F32>(head, hoff + e + half);
+            float r0 = x0 * cs - x1 * sn, r1 = x1 * cs + x0 * sn;
+            store_elem<F32>(head, hoff + e, r0);
+            store_elem<F32>(head, hoff + e + half, r1);
+            if (dst) { dst[e] = f32_to_bf16_bits(r0); dst[e + half] = f32_to_bf16_bits(r1); }
         }
     } else {
         uint16_t* dst = vc + ((row * cap + pos) * n_kv + (slot - n_q - n_kv)) * d;
-        for (int64_t e = lane; e < d; e += 64) dst[e] = head[e];
+        for (int64_t e = lane; e < d; e += 64) dst[e] = f32_to_bf16_bits(load_elem<F32>(head, hoff + e));
     }
 }
 
@@ -337,7 +348,8 @@ int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& ato
         else      { if (out32) L2(bias_act_kernel, false, true); else L2(bias_act_kernel, false, false); }
         break;
     case LITHOS_OP_SILU_MUL:
-        e = launch_kernel(silu_mul_kernel, grid, block, s, a, atom);
+        if (in32) { if (out32) L2(silu_mul_kernel, true, true); else L2(silu_mul_kernel, true, false); }
+        else      { if (out32) L2(silu_mul_kernel, false, true); else L2(silu_mul_kernel, false, false); }
         break;
     case LITHOS_OP_LAYERNORM:
         if (tpr_for(a.cols) == 64) {
@@ -349,8 +361,13 @@ int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& ato
         }
         break;
     case LITHOS_OP_RMSNORM:
-        if (tpr_for(a.cols) == 64) { if (in32) L2(rmsnorm_kernel, true, 64); else L2(rmsnorm_kernel, false, 64); }
-        else                       { if (in32) L2(rmsnorm_kernel, true, 256); else L2(rmsnorm_kernel, false, 256); }
+        if (tpr_for(a.cols) == 64) {
+            if (in32) { if (out32) L3(rmsnorm_kernel, true, true, 64); else L3(rmsnorm_kernel, true, false, 64); }
+            else      { if (out32) L3(rmsnorm_kernel, false, true, 64); else L3(rmsnorm_kernel, false, false, 64); }
+        } else {
+            if (in32) { if (out32) L3(rmsnorm_kernel, true, true, 256); else L3(rmsnorm_kernel, true, false, 256); }
+            else      { if (out32) L3(rmsnorm_kernel, false, true, 256); else L3(rmsnorm_kernel, false, false, 256); }
+        }
         break;
     case LITHOS_OP_SOFTMAX:
         if (tpr_for(a.cols) == 64) {
@@ -365,7 +382,8 @@ int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& ato
         a.cols = op.dim[3];
         a.aux[0] = op.dim[1]; a.aux[1] = op.dim[2]; a.aux[2] = op.dim[4]; a.aux[3] = op.dim[5];
         a.p0 = nullptr; a.p1 = nullptr;
-        e = launch_kernel(rope_kv_kernel, grid, block, s, a, atom);
+        if (in32) e = launch_kernel(rope_kv_kernel<true>, grid, block, s, a, atom);
+        else e = launch_kernel(rope_kv_kernel<false>, grid, block, s, a, atom);
         break;
     case LITHOS_OP_SPIN:
         e = launch_kernel(spin_kernel, grid, block, s, (uint64_t)op.dim[1], atom);

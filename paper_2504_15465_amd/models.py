@@ -8,9 +8,13 @@ Edge dtypes (what is stored between two kernels):
 * MLP layer        GEMM(+bias+GELU) -> fp32; LayerNorm -> fp32.  The batch is
                    small, so the GEMM is the weight-streaming kind, which
                    reads fp32 activations against bf16 weights.
-* encoder layer    QKV GEMM -> bf16; attention -> bf16; out-proj(+bias+residual) -> fp32;
-                   LayerNorm -> fp32 + bf16 copy; FFN1(+bias+GELU) -> bf16;
-                   FFN2(+bias+residual) -> fp32; LayerNorm -> fp32 + bf16 copy
+* encoder layer    QKV GEMM -> bf16; attention -> split bf16; out-proj(+bias+residual) -> fp32;
+                   LayerNorm -> fp32 + split bf16; FFN1(+bias+GELU) -> split bf16;
+                   FFN2(+bias+residual) -> fp32; LayerNorm -> fp32 + split bf16.
+                   "Split bf16" = two bf16 planes hi + lo (~16 significant bits): the
+                   MFMA GEMMs multiply both planes with the same weights, so the GEMM
+                   inputs carry no coarse rounding that another implementation could
+                   round the other way.
 * decoder layer    every edge fp32 (weight-streaming GEMMs), except the
                    key/value cache, which is bf16: the current token's rotated
                    key and its value are rounded when appended.
@@ -91,3 +95,116 @@ def run_ops(ctx, ops, part=None, atom_blocks=0):
     for op in ops:
         B.lithos_launch_atomized(ctx, op, (0, 0, 0), atom_blocks, part, None)
     B.lithos_partition_sync(ctx, part)
+
+
+class EncoderChain:
+    """Post-LayerNorm encoder stack (QKV GEMM, full attention, out-proj + residual,
+    LayerNorm, FFN with GELU + residual, LayerNorm) on [batch*seq, hidden] tokens.
+    The residual stream is fp32; GEMM inputs are its bf16 copy."""
+
+    def __init__(self, layers, batch: int, seq: int = 128, heads: int = 12, device="cuda", tile: int = B.TILE_AUTO):
+        self.batch, self.seq, self.heads = batch, seq, heads
+        H = layers[0]["w_qkv"].shape[0]
+        F = layers[0]["w_1"].shape[1]
+        T = batch * seq
+        self.H, self.F, self.T, self.tile = H, F, T, tile
+        self.d = H // heads
+        self.p = []
+        for L in layers:
+            self.p.append({k: (_dev(v, device) if v.dtype == np.uint16 else _f32(v, device)) for k, v in L.items()})
+        bf, f32 = torch.bfloat16, torch.float32
+        self.x = torch.zeros((T, H), dtype=f32, device=device)          # input copy
+        self.h32 = torch.zeros((T, H), dtype=f32, device=device)        # residual stream
+        self.hb = torch.zeros((2, T, H), dtype=bf, device=device)       # hi, lo planes
+        self.qkv = torch.zeros((T, 3 * H), dtype=bf, device=device)
+        self.att = torch.zeros((2, T, H), dtype=bf, device=device)
+        self.r = torch.zeros((T, H), dtype=f32, device=device)
+        self.f = torch.zeros((2, T, F), dtype=bf, device=device)
+        self.one = torch.ones((H,), dtype=f32, device=device)
+        self.zero = torch.zeros((H,), dtype=f32, device=device)
+        self.out = self.h32
+
+    def ops(self) -> List[B.Op]:
+        T, H, F, t = self.T, self.H, self.F, self.tile
+        ops = [
+            B.bias_act_op(self.x, self.h32, T, H, None, gelu=False),     # working copy of the input
+        ]
+        first = True
+        for P in self.p:
+            if first:      # hi/lo planes of the input hidden states for the first GEMM
+                first = False
+                ops.append(B.split_op(self.x, self.hb, T, H))
+            ops += [
+                B.gemm_op(self.hb, P["w_qkv"], self.qkv, T, 3 * H, H, bias=P["b_qkv"], tile=t, a_split=True),
+                B.attn_enc_op(self.qkv, self.att, self.batch, self.heads, self.seq, self.d, 1.0 / math.sqrt(self.d), split=True),
+                B.gemm_op(self.att, P["w_o"], self.r, T, H, H, bias=P["b_o"], residual=self.h32, tile=t, a_split=True),
+                B.layernorm_op(self.r, P["ln1_g"], P["ln1_b"], self.h32, T, H, y_bf16=self.hb, split=True),
+                B.gemm_op(self.hb, P["w_1"], self.f, T, F, H, bias=P["b_1"], gelu=True, tile=t, a_split=True, c_split=True),
+                B.gemm_op(self.f, P["w_2"], self.r, T, H, F, bias=P["b_2"], residual=self.h32, tile=t, a_split=True),
+                B.layernorm_op(self.r, P["ln2_g"], P["ln2_b"], self.h32, T, H, y_bf16=self.hb, split=True),
+            ]
+        for i, o in enumerate(ops):
+            o.op_id = i
+        return ops
+
+    def set_input(self, x32: np.ndarray):
+        self.x.copy_(torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)))
+
+
+class DecoderChain:
+    """One decode step of a pre-norm grouped-query decoder stack against a bf16
+    key/value cache.  All GEMMs are the weight-streaming kind (weights [N,K],
+    fp32 activations); the cache slot ``pos`` is rewritten on every step."""
+
+    def __init__(self, layers, kcache_bits, vcache_bits, batch: int, n_q: int, n_kv: int, pos: int, device="cuda"):
+        self.batch, self.n_q, self.n_kv, self.pos = batch, n_q, n_kv, pos
+        H = layers[0]["w_qkv"].shape[0]
+        self.H = H
+        self.d = H // n_q
+        self.F = layers[0]["w_d"].shape[0]
+        self.cap = pos + 1
+        self.w = []
+        for L in layers:
+            self.w.append(dict(rms1=_f32(L["rms1"], device), rms2=_f32(L["rms2"], device),
+                               w_qkv=_wt(L["w_qkv"], device), w_o=_wt(L["w_o"], device),
+                               w_gu=_wt(L["w_gu"], device), w_d=_wt(L["w_d"], device)))
+        self.kc, self.vc = [], []
+        for kb, vb in zip(kcache_bits, vcache_bits):
+            for src, dst in ((kb, self.kc), (vb, self.vc)):
+                c = torch.zeros((batch, self.cap, n_kv, self.d), dtype=torch.bfloat16, device=device)
+                c[:, :pos].copy_(bits_to_torch(src))
+                dst.append(c)
+        f32 = torch.float32
+        nqkv = (n_q + 2 * n_kv) * self.d
+        self.x_in = torch.zeros((batch, H), dtype=f32, device=device)
+        self.x = torch.zeros((batch, H), dtype=f32, device=device)
+        self.n = torch.zeros((batch, H), dtype=f32, device=device)
+        self.qkv = torch.zeros((batch, nqkv), dtype=f32, device=device)
+        self.att = torch.zeros((batch, n_q * self.d), dtype=f32, device=device)
+        self.gu = torch.zeros((batch, 2 * self.F), dtype=f32, device=device)
+        self.act = torch.zeros((batch, self.F), dtype=f32, device=device)
+        self.out = self.x
+
+    def ops(self) -> List[B.Op]:
+        Bn, H, F, d, n_q, n_kv = self.batch, self.H, self.F, self.d, self.n_q, self.n_kv
+        nqkv = (n_q + 2 * n_kv) * d
+        ops = [B.bias_act_op(self.x_in, self.x, Bn, H, None, gelu=False)]      # working copy of the input
+        for li, W in enumerate(self.w):
+            ops += [
+                B.rmsnorm_op(self.x, W["rms1"], self.n, Bn, H),
+                B.gemm_op(self.n, W["w_qkv"], self.qkv, Bn, nqkv, H, tb=True),
+                B.rope_kv_op(self.qkv, self.kc[li], self.vc[li], Bn, n_q, n_kv, d, self.pos, self.cap),
+                B.attn_dec_op(self.qkv, self.kc[li], self.vc[li], self.att, Bn, n_q, n_kv, d, self.pos + 1, self.cap,
+                              1.0 / math.sqrt(d), ldq=nqkv),
+                B.gemm_op(self.att, W["w_o"], self.x, Bn, H, n_q * d, tb=True, residual=self.x),
+                B.rmsnorm_op(self.x, W["rms2"], self.n, Bn, H),
+                B.gemm_op(self.n, W["w_gu"], self.gu, Bn, 2 * F, H, tb=True),
+                B.silu_mul_op(self.gu, self.act, Bn, F),
+                B.gemm_op(self.act, W["w_d"], self.x, Bn, H, F, tb=True, residual=self.x),
+            ]
+        for i, o in enumerate(ops):
+            o.op_id = i
+        return ops
+
+    def set_input(self, x32: np.ndarray):
+        self.x_in.copy_(torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)))

@@ -1,0 +1,142 @@
+"""GPU parity of the attention kernels and of the encoder / decoder chains."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import models as OM
+from oracle import ops as O
+from paper_2504_15465_amd import binding as B
+from paper_2504_15465_amd import inputs
+from paper_2504_15465_amd.models import DecoderChain, EncoderChain, run_ops
+from gpu_util import bits_equal, bf16_close, counters, ctx, dev_bits, nan_like
+
+pytestmark = pytest.mark.gpu
+
+E2E_TOL = 1e-2
+
+
+def launch(op, atom_blocks=0):
+    grid, _ = B.lithos_op_grid(ctx(), op)
+    total = grid[0] * grid[1] * grid[2]
+    cnt = counters(total)
+    B.lithos_debug_block_counters(ctx(), cnt)
+    torch.cuda.synchronize()
+    try:
+        B.lithos_launch_atomized(ctx(), op, (0, 0, 0), atom_blocks, None, None)
+        B.lithos_partition_sync(ctx(), None)
+    finally:
+        B.lithos_debug_block_counters(ctx(), None)
+    assert cnt.cpu().tolist() == [1] * total
+    return total
+
+
+@pytest.mark.parametrize("batch,heads,seq", [(1, 12, 128), (3, 5, 128), (2, 3, 64), (1, 2, 256)])
+def test_encoder_attention(batch, heads, seq):
+    d = 64
+    bits = inputs.normal_bits((batch * seq, 3 * heads * d), 40, 0.7)
+    qkv = O.bf16_to_f64(bits).reshape(batch, seq, 3, heads, d)
+    ref = O.attention(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], 1 / math.sqrt(d)).reshape(batch * seq, heads * d)
+    o = nan_like((batch * seq, heads * d), torch.bfloat16)
+    x = dev_bits(bits)
+    total = launch(B.attn_enc_op(x, o, batch, heads, seq, d, 1 / math.sqrt(d)))
+    assert total == batch * heads
+    # probabilities are rounded to bf16 before the value product: 2^-9 relative per term,
+    # averaged over the keys; outputs are O(0.1), so a few 1e-4 absolute on top of the output rounding
+    g = o.cpu().to(torch.float64).numpy()
+    assert np.abs(g - ref).max() <= 6e-3
+    assert np.abs(g - ref).mean() <= 6e-4
+    oa = nan_like(o.shape, torch.bfloat16)
+    launch(B.attn_enc_op(x, oa, batch, heads, seq, d, 1 / math.sqrt(d)), atom_blocks=2)
+    assert bits_equal(o, oa)
+
+
+def test_encoder_attention_special_cases():
+    batch, heads, seq, d = 1, 2, 128, 64
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((batch * seq, 3, heads, d)).astype(np.float32)
+    x[:, 2] = np.broadcast_to(rng.standard_normal((1, heads, d)), (seq, heads, d))     # constant values
+    bits = inputs.to_bf16_bits(x.reshape(batch * seq, -1))
+    o = nan_like((batch * seq, heads * d), torch.bfloat16)
+    launch(B.attn_enc_op(dev_bits(bits), o, batch, heads, seq, d, 0.125))
+    v = O.bf16_to_f64(bits).reshape(seq, 3, heads, d)[0, 2].reshape(-1)
+    g = o.cpu().to(torch.float64).numpy()
+    assert np.abs(g - v[None, :]).max() <= 2.0 ** -7 * np.abs(v).max() + 1e-3       # O = V when V is constant
+
+
+@pytest.mark.parametrize("batch,n_q,n_kv,keys", [(1, 32, 8, 2049), (3, 8, 8, 70), (2, 4, 2, 300), (16, 32, 8, 257)])
+@pytest.mark.parametrize("q32", [True, False])
+def test_decode_attention(batch, n_q, n_kv, keys, q32):
+    d, cap = 128, keys + 3
+    qb = inputs.normal_bits((batch, n_q * d), 41)
+    kb = inputs.normal_bits((batch, cap, n_kv, d), 42)
+    vb = inputs.normal_bits((batch, cap, n_kv, d), 43)
+    q64 = O.bf16_to_f64(qb).reshape(batch, 1, n_q, d)
+    ref = O.attention(q64, O.bf16_to_f64(kb)[:, :keys], O.bf16_to_f64(vb)[:, :keys], 1 / math.sqrt(d)).reshape(batch, n_q * d)
+    q = dev_bits(qb)
+    if q32:
+        q = q.float()
+    o = nan_like((batch, n_q * d), torch.float32 if q32 else torch.bfloat16)
+    k, v = dev_bits(kb), dev_bits(vb)
+    total = launch(B.attn_dec_op(q, k, v, o, batch, n_q, n_kv, d, keys, cap, 1 / math.sqrt(d)))
+    assert total == batch * n_kv
+    if q32:
+        assert np.abs(o.cpu().numpy().astype(np.float64) - ref).max() <= 2e-5
+    else:
+        bf16_close(o, ref, abs_tol=2e-5)
+    oa = nan_like(o.shape, o.dtype)
+    launch(B.attn_dec_op(q, k, v, oa, batch, n_q, n_kv, d, keys, cap, 1 / math.sqrt(d)), atom_blocks=3)
+    assert bits_equal(o, oa)
+
+
+def test_attention_refuses_unbuilt_shapes():
+    x = torch.zeros((128, 3 * 64), dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros((128, 64), dtype=torch.bfloat16, device="cuda")
+    bad = [B.attn_enc_op(x, o, 1, 1, 128, 32, 1.0), B.attn_enc_op(x, o, 1, 1, 100, 64, 1.0),
+           B.attn_dec_op(x, x, x, o, 1, 6, 2, 128, 4, 4, 1.0),      # group of 3
+           B.attn_dec_op(x, x, x, o, 1, 4, 4, 64, 4, 4, 1.0),       # head width 64
+           B.attn_dec_op(x, x, x, o, 1, 4, 4, 128, 9, 4, 1.0)]      # more keys than the cache holds
+    for op in bad:
+        with pytest.raises(B.LithosError) as e:
+            B.lithos_launch_atomized(ctx(), op)
+        assert e.value.code == B.EINVAL
+
+
+@pytest.mark.parametrize("batch,n_layers", [(1, 12), (4, 3)])
+def test_encoder_chain_matches_oracle(batch, n_layers):
+    """Config-3 high-priority tenant: hidden 768, 12 heads, seq 128, post-LayerNorm."""
+    layers = inputs.encoder_params(n_layers, 768, 3072, seed=10)
+    x = inputs.encoder_hidden(batch, 128, 768, seed=11)
+    chain = EncoderChain(layers, batch, 128, 12)
+    chain.set_input(x)
+    run_ops(ctx(), chain.ops())
+    out = chain.out.clone()
+    ref = OM.encoder_forward(x, layers, batch, 128, 12)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    assert err.max() <= E2E_TOL, (err.max(), err.mean())
+    part = B.lithos_create_partition(ctx(), B.lithos_make_mask(ctx(), 64))
+    try:
+        run_ops(ctx(), chain.ops(), part, atom_blocks=7)
+        assert bits_equal(chain.out, out)
+    finally:
+        B.lithos_destroy_partition(part)
+
+
+@pytest.mark.parametrize("batch,n_layers,pos", [(1, 2, 2048), (16, 1, 2048), (3, 2, 100)])
+def test_decoder_chain_matches_oracle(batch, n_layers, pos):
+    """Config-5 high-priority tenant at its real per-layer shape (hidden 4096, 32/8 heads, FFN 14336)."""
+    H, n_q, n_kv, F = 4096, 32, 8, 14336
+    layers = inputs.decoder_params(n_layers, H, n_q, n_kv, F, seed=20)
+    ks, vs = inputs.decoder_kv_cache(n_layers, batch, pos, n_kv, H // n_q, seed=21)
+    x = inputs.decoder_hidden(batch, H, seed=22)
+    chain = DecoderChain(layers, ks, vs, batch, n_q, n_kv, pos)
+    chain.set_input(x)
+    run_ops(ctx(), chain.ops())
+    out = chain.out.clone()
+    ref = OM.decoder_decode_step(x, layers, ks, vs, n_q, n_kv, pos)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    assert err.max() <= E2E_TOL, (err.max(), err.mean())
+    assert err.max() <= 2e-3
+    run_ops(ctx(), chain.ops(), None, atom_blocks=5)
+    assert bits_equal(chain.out, out)

@@ -186,3 +186,31 @@ def test_bad_arguments_are_refused_before_launch():
         B.lithos_launch_atom(ctx(), op, 0, 2)                 # beyond the single block
     B.lithos_launch_atomized(ctx(), op, grid=(1, 1, 1))       # same total, other factorisation: fine
     B.lithos_partition_sync(ctx(), None)
+
+
+@pytest.mark.parametrize("tile,tb", [(64, False), (128, True), (128, False)])
+def test_split_bf16_activations_and_outputs(tile, tb):
+    """A given as hi + lo bf16 planes (~16 significant bits) and C written as such a pair."""
+    m, n, k = 200, 264, 328
+    x32 = inputs.normal_f32((m, k), 50)
+    hi = inputs.to_bf16_bits(x32)
+    lo = inputs.to_bf16_bits(x32 - O.bf16_to_f64(hi).astype(np.float32))
+    b_bits = inputs.normal_bits((n, k) if tb else (k, n), 51, 0.05)
+    a_val = O.bf16_to_f64(hi) + O.bf16_to_f64(lo)
+    assert np.array_equal(a_val, O.round_bf16x2(x32.astype(np.float64)))      # same split as the oracle's
+    ref = O.gemm(a_val, b_bits, tb=tb)
+    a_pair = dev_bits(np.stack([hi, lo]))
+    b = dev_bits(b_bits)
+    c = nan_like((m, n), torch.float32)
+    torch.cuda.synchronize()
+    B.lithos_launch_atomized(ctx(), B.gemm_op(a_pair, b, c, m, n, k, tb=tb, tile=tile, a_split=True))
+    B.lithos_partition_sync(ctx(), None)
+    assert rel_fro(c, ref) <= 1e-6          # far tighter than the bf16-input bar: the lo plane is really used
+    # bf16 pair output
+    cp = nan_like((2, m, n), torch.bfloat16)
+    B.lithos_launch_atomized(ctx(), B.gemm_op(a_pair, b, cp, m, n, k, tb=tb, tile=tile, a_split=True, c_split=True), (0, 0, 0), 3)
+    B.lithos_partition_sync(ctx(), None)
+    got = cp[0].cpu().to(torch.float64).numpy() + cp[1].cpu().to(torch.float64).numpy()
+    assert np.abs(got - ref).max() <= 2.0 ** -15 * np.abs(ref).max() + 1e-6
+    with pytest.raises(B.LithosError):
+        B.lithos_launch_atomized(ctx(), B.gemm_op(a_pair, b, c, m, n, k, tb=tb, tile=256, a_split=True))

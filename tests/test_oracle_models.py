@@ -21,6 +21,12 @@ def bf(t):
     return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
 
 
+def bf2(t):
+    """split-bf16 edge: hi + lo with hi = bf16(t), lo = bf16(t - hi)."""
+    hi = bf(t)
+    return hi + bf(t - hi)
+
+
 def w64(bits):
     return inputs.bits_to_torch(bits).to(torch.float64)
 
@@ -54,12 +60,12 @@ def test_encoder_chain_against_torch():
     h = torch.from_numpy(x).double()
     tv = lambda L, n: torch.from_numpy(L[n]).double()
     for L in layers:
-        qkv = bf(bf(h) @ w64(L["w_qkv"]) + tv(L, "b_qkv"))
+        qkv = bf(bf2(h) @ w64(L["w_qkv"]) + tv(L, "b_qkv"))
         q, k, v = [t.reshape(Bn, S, heads, d).permute(0, 2, 1, 3) for t in qkv.split(H, dim=1)]
         att = F.scaled_dot_product_attention(q, k, v).permute(0, 2, 1, 3).reshape(Bn * S, H)
-        r1 = bf(att) @ w64(L["w_o"]) + tv(L, "b_o") + h
+        r1 = bf2(att) @ w64(L["w_o"]) + tv(L, "b_o") + h
         h1 = F.layer_norm(r1, (H,), tv(L, "ln1_g"), tv(L, "ln1_b"), 1e-5)
-        f = bf(F.gelu(bf(h1) @ w64(L["w_1"]) + tv(L, "b_1")))
+        f = bf2(F.gelu(bf2(h1) @ w64(L["w_1"]) + tv(L, "b_1")))
         r2 = f @ w64(L["w_2"]) + tv(L, "b_2") + h1
         h = F.layer_norm(r2, (H,), tv(L, "ln2_g"), tv(L, "ln2_b"), 1e-5)
     diff = np.abs(got - h.numpy())

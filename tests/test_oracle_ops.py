@@ -277,3 +277,15 @@ def test_silu_mul_closed_forms():
     assert abs(y[3] - 30.0) < 1e-11 and abs(y[4]) < 1e-11
     ref = torch.nn.functional.silu(torch.from_numpy(g)) * torch.from_numpy(u)
     assert np.allclose(y, ref.numpy(), atol=1e-15)
+
+
+def test_split_bf16_pair_properties():
+    rng = np.random.default_rng(12)
+    x = np.concatenate([rng.standard_normal(5000) * 3, [1.0, 1 + 2.0**-8, 1 + 2.0**-9, 0.0, -2.5]])
+    v = ops.round_bf16x2(x)
+    hi = ops.round_bf16(x)
+    assert np.array_equal(v, hi + ops.round_bf16(x - hi))
+    nz = x != 0
+    assert np.all(np.abs(v[nz] - x[nz]) <= 2.0**-17 * np.abs(x[nz]))     # two 8-bit significands
+    assert ops.round_bf16x2(np.array([1 + 2.0**-9]))[0] == 1 + 2.0**-9   # exactly representable as a pair
+    assert np.array_equal(ops.round_bf16x2(hi), hi)                     # bf16 values split as (v, 0)
