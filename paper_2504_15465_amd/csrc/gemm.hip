@@ -4,9 +4,11 @@
 //  * gemm_tile_kernel  - MFMA (v_mfma_f32_32x32x16_bf16) on LDS-staged tiles of
 //    64x64, 128x128 or 256x256 outputs, BK = 64, 4 wavefronts per workgroup;
 //  * gemm_skinny_kernel - M <= 32 rows (bf16 or fp32 activations) against a
-//    [N,K] bf16 weight matrix: the weights are streamed once from HBM with
-//    16-byte loads and multiplied on the vector ALUs (the op is HBM-bound;
-//    reshaping it for MFMA buys nothing).
+//    [N,K] bf16 weight matrix: HBM-bound, the weights are streamed exactly
+//    once with 16-byte loads.  The products still go through MFMA 16x16x32
+//    (weights as the row operand, activations padded to 16 rows): on a 64-CU
+//    partition the plain vector ALUs would need longer for the 2*M*N*K flops
+//    than HBM needs for the weights.
 //
 // Every workgroup computes the output tile named by its LOGICAL block index
 // (LithOS Section 4.4), so a launch of any sub-range of blocks writes exactly
@@ -45,6 +47,19 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 __device__ __forceinline__ float gelu_erf(float u)
 {
     return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
+}
+
+// Compile-time loop: the body sees its index as a constant, so register
+// arrays indexed with it never become memory.
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 __device__ __forceinline__ void epilogue_store(const GemmArgs& g, int m, int n, float v)
@@ -174,11 +189,11 @@ __device__ __forceinline__ void tile_of_block(uint32_t lin, uint32_t tiles_m, ui
 
 // SPLIT: A is a pair of bf16 planes (hi, lo) whose sum carries ~16 significant
 // bits of the activation; both planes are multiplied with the same B operand.
-template <int BM, int BN, bool TA, bool TB, bool SPLIT>
-__global__ __launch_bounds__(256)
+template <int BM, int BN, int WGM, int WGN, bool TA, bool TB, bool SPLIT>
+__global__ __launch_bounds__(WGM * WGN * 64)
 void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 {
-    constexpr int T = 256, BK = 64, WGM = 2, WGN = 2;
+    constexpr int T = WGM * WGN * 64, BK = 64;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     __shared__ __attribute__((aligned(16))) uint16_t As[BM * BK];
     __shared__ __attribute__((aligned(16))) uint16_t As2[SPLIT ? BM * BK : 8];
@@ -255,166 +270,154 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 
     // 32x32 accumulator block: lane holds column (lane & 31); element e is
     // row 8*(e/4) + 4*(lane/32) + e%4.
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            int n = n0 + wn * WN + j * 32 + (lane & 31);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                int m = m0 + wm * WM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                epilogue_store(g, m, n, acc[i][j][e]);
-            }
-        }
+    static_for<MI * NI>([&](auto ij) {
+        constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
+        const int n = n0 + wn * WN + j * 32 + (lane & 31);
+        const int mb = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
+        static_for<16>([&](auto ee) {
+            constexpr int e = decltype(ee)::value;
+            epilogue_store(g, mb + 8 * (e >> 2) + (e & 3), n, acc[i][j][e]);
+        });
+    });
 }
 
-// ---- skinny: M <= MT rows, B stored [N,K] ---------------------------------
-// A workgroup owns 16 output columns (4 per wavefront) and walks K in stages
-// of KC.  The activations x[:, stage] are staged in LDS (fp32 when the op
-// gives fp32 activations, else bf16); each lane multiplies eight consecutive k
-// of four weight rows with the same eight k of every x row, and a butterfly
-// over the 64 lanes finishes each dot product.  The next stage's x and
-// weights are already in flight (in registers) while the current one is
-// computed.  Lane order and stage order are fixed, so the result is a pure
-// function of the logical block index.
-template <int MT, bool A32>
-struct SkinnyStage {
-    static constexpr int KC0 = (A32 ? 8192 : 16384) / MT;     // 32 KB of x per stage ...
-    static constexpr int KC = KC0 < 512 ? 512 : KC0;          // ... but at least one k-step per lane
-    static constexpr int LDS_BYTES = MT * KC * (A32 ? 4 : 2);
-    static constexpr int XV = LDS_BYTES / 16 / 256;           // 16-byte x registers per thread
-    static constexpr int IT = KC / 512;                       // k-steps per lane per stage
-    static constexpr int NC = 4;
-    uint4 x[XV];
-    uint4 w[IT][NC];
+// ---- skinny: M <= 32 rows, B stored [N,K] -----------------------------------
+// out[m][n] = sum_k x[m][k] W[n][k] on MFMA 16x16x32 with the WEIGHTS as the
+// row operand: D[n][m] += W[n][k..k+31] x[m][k..k+31].  A workgroup owns 16*NB
+// output columns; its four wavefronts split K in quarters and their partial
+// tiles are added in wave order through LDS.  Every lane streams 16 bytes of
+// one weight row per step (64 contiguous bytes per row and step, rows walked
+// sequentially), so the weight matrix is read from HBM exactly once.
+// fp32 activations are fed exactly: x = hi + mid + lo with three bf16 values
+// (8 + 8 + 8 significant bits), three MFMAs per weight operand.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-    __device__ __forceinline__ void load(const GemmArgs& g, const uint16_t* const (&wrow)[NC], int k0, int tid, int lane)
-    {
+__device__ __forceinline__ bf16x8 pack_hi16(const float (&v)[8])
+{
+    // keep the upper 16 bits of each fp32 (truncation): a bf16 value
+    uint32_t w[4];
 #pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            int k = k0 + it * 512 + lane * 8;
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (k < g.K) v = *reinterpret_cast<const uint4*>(wrow[c] + k);
-                w[it][c] = v;
-            }
-        }
-        constexpr int EPV = A32 ? 4 : 8;                      // elements per 16-byte register
-#pragma unroll
-        for (int i = 0; i < XV; ++i) {
-            int c = tid + i * 256;
-            int m = c / (KC / EPV), kk = (c % (KC / EPV)) * EPV;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (m < g.M && k0 + kk < g.K) {
-                if constexpr (A32) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(g.A) + (int64_t)m * g.lda + k0 + kk);
-                else v = *reinterpret_cast<const uint4*>(g.A + (int64_t)m * g.lda + k0 + kk);
-            }
-            x[i] = v;
-        }
-    }
+    for (int p = 0; p < 4; ++p)
+        w[p] = (__float_as_uint(v[2 * p]) >> 16) | (__float_as_uint(v[2 * p + 1]) & 0xffff0000u);
+    return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+}
 
-    // fp32 layout in LDS: the two halves (k%8 < 4, k%8 >= 4) of every 8-group
-    // live in separate planes, so the 64 lanes read consecutive 16-byte slots.
-    __device__ __forceinline__ void store(void* lds, int tid) const
-    {
-        constexpr int EPV = A32 ? 4 : 8;
-#pragma unroll
-        for (int i = 0; i < XV; ++i) {
-            int c = tid + i * 256;
-            int m = c / (KC / EPV), kk = (c % (KC / EPV)) * EPV;
-            if constexpr (A32) {
-                int grp = kk >> 3, half = (kk >> 2) & 1;
-                reinterpret_cast<uint4*>(lds)[(m * KC + half * (KC / 2)) / 4 + grp] = x[i];
-            } else {
-                reinterpret_cast<uint4*>(lds)[(m * KC + kk) / 8] = x[i];
-            }
-        }
-    }
-};
-
-template <int MT, bool A32>
+template <int MB, int NB, bool A32>
 __global__ __launch_bounds__(256)
 void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
 {
-    using Stage = SkinnyStage<MT, A32>;
-    constexpr int KC = Stage::KC, NC = Stage::NC, IT = Stage::IT;
-    __shared__ __attribute__((aligned(16))) unsigned char xs_raw[Stage::LDS_BYTES];
+    constexpr int U = 4;                        // k-steps whose loads are in flight together
+    __shared__ __attribute__((aligned(16))) float red[4][MB][NB][64][4];
 
     const uint32_t L = atom_logical_block(atom);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nbase = (int)L * 16 + wave * NC;
+    const int r16 = lane & 15, kg = lane >> 4;
+    const int n0 = (int)L * 16 * NB;
+    // this wavefront's K range: quarters rounded to whole 32-wide steps
+    const int kq = ((g.K + 127) / 128) * 32;
+    const int kbeg = wave * kq, kend = min(g.K, kbeg + kq);
 
-    float acc[MT][NC];
+    f32x4 acc[MB][NB];
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int c = 0; c < NC; ++c) acc[m][c] = 0.0f;
+        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const uint16_t* wrow[NC];
+    const uint16_t* wrow[NB];
 #pragma unroll
-    for (int c = 0; c < NC; ++c) wrow[c] = g.B + (int64_t)min(nbase + c, g.N - 1) * g.ldb;
+    for (int j = 0; j < NB; ++j) wrow[j] = g.B + (int64_t)min(n0 + j * 16 + r16, g.N - 1) * g.ldb;
+    bool mlive[MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) mlive[i] = (i * 16 + r16) < g.M;
 
-    Stage cur, nxt;
-    cur.load(g, wrow, 0, tid, lane);
-    for (int k0 = 0; k0 < g.K; k0 += KC) {
-        cur.store(xs_raw, tid);
-        __syncthreads();
-        if (k0 + KC < g.K) nxt.load(g, wrow, k0 + KC, tid, lane);
+    for (int k0 = kbeg; k0 < kend; k0 += 32 * U) {
+        uint4 wv[U][NB];
+        uint4 xv[U][MB][A32 ? 2 : 1];
 #pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            const int kk = it * 512 + lane * 8;          // offset inside the stage
-            float wf[NC][8];
+        for (int u = 0; u < U; ++u) {
+            const int k = k0 + u * 32 + kg * 8;
+            const bool klive = k < kend;
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const uint4 v = cur.w[it][c];
-                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    wf[c][2 * p] = __uint_as_float(u[p] << 16);
-                    wf[c][2 * p + 1] = __uint_as_float(u[p] & 0xffff0000u);
-                }
+            for (int j = 0; j < NB; ++j) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (klive) v = *reinterpret_cast<const uint4*>(wrow[j] + k);
+                wv[u][j] = v;
             }
 #pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                float xf[8];
-                if constexpr (A32) {
-                    const float* xl = reinterpret_cast<const float*>(xs_raw);
-                    const float4 lo = *reinterpret_cast<const float4*>(xl + m * KC + (kk >> 3) * 4);
-                    const float4 hi = *reinterpret_cast<const float4*>(xl + m * KC + KC / 2 + (kk >> 3) * 4);
-                    xf[0] = lo.x; xf[1] = lo.y; xf[2] = lo.z; xf[3] = lo.w;
-                    xf[4] = hi.x; xf[5] = hi.y; xf[6] = hi.z; xf[7] = hi.w;
-                } else {
-                    const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(xs_raw) + m * KC + kk);
-                    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {
-                        xf[2 * p] = __uint_as_float(u[p] << 16);
-                        xf[2 * p + 1] = __uint_as_float(u[p] & 0xffff0000u);
+            for (int i = 0; i < MB; ++i) {
+                uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+                if (klive && mlive[i]) {
+                    if constexpr (A32) {
+                        const float* xp = reinterpret_cast<const float*>(g.A) + (int64_t)(i * 16 + r16) * g.lda + k;
+                        v0 = *reinterpret_cast<const uint4*>(xp);
+                        v1 = *reinterpret_cast<const uint4*>(xp + 4);
+                    } else {
+                        v0 = *reinterpret_cast<const uint4*>(g.A + (int64_t)(i * 16 + r16) * g.lda + k);
                     }
                 }
-#pragma unroll
-                for (int c = 0; c < NC; ++c)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[m][c] = fmaf(xf[e], wf[c][e], acc[m][c]);
+                xv[u][i][0] = v0;
+                if constexpr (A32) xv[u][i][1] = v1;
             }
         }
-        __syncthreads();
-        cur = nxt;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                if constexpr (A32) {
+                    float x[8], r1[8], r2[8];
+                    const uint4 a = xv[u][i][0], b = xv[u][i][1];
+                    const uint32_t raw[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        x[e] = __uint_as_float(raw[e]);
+                        r1[e] = x[e] - __uint_as_float(raw[e] & 0xffff0000u);               // exact
+                        r2[e] = r1[e] - __uint_as_float(__float_as_uint(r1[e]) & 0xffff0000u);  // exact, <= 8 bits
+                    }
+                    const bf16x8 xh = pack_hi16(x), xm = pack_hi16(r1), xl = pack_hi16(r2);
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) {
+                        const bf16x8 wf = __builtin_bit_cast(bf16x8, wv[u][j]);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xl, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xm, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xh, acc[i][j], 0, 0, 0);
+                    }
+                } else {
+                    const bf16x8 xf = __builtin_bit_cast(bf16x8, xv[u][i][0]);
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[u][j]), xf,
+                                                                             acc[i][j], 0, 0, 0);
+                }
+            }
+        }
     }
 
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            float v = acc[m][c];
+        for (int j = 0; j < NB; ++j)
+            *reinterpret_cast<f32x4*>(&red[wave][i][j][lane][0]) = acc[i][j];
+    __syncthreads();
+    if (wave == 0) {
+        // accumulator element e of a lane is D[n = 4*kg + e][m = r16]
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-            if (lane == ((m * NC + c) & 63)) epilogue_store(g, m, nbase + c, v);
-        }
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = red[0][i][j][lane][e];
+                    v += red[1][i][j][lane][e];
+                    v += red[2][i][j][lane][e];
+                    v += red[3][i][j][lane][e];
+                    epilogue_store(g, i * 16 + r16, n0 + j * 16 + 4 * kg + e, v);
+                }
+    }
 }
 
 // ---- host side -------------------------------------------------------------
+
+constexpr int SKINNY_NB = 2;        // 16-column blocks per workgroup of the skinny kernel
 
 enum { V_SKINNY8 = 1, V_SKINNY16 = 2, V_SKINNY32 = 3, V_TILE64 = 10, V_TILE128 = 20, V_TILE256 = 30 };
 
@@ -422,30 +425,32 @@ typedef void (*gemm_fn)(GemmArgs, AtomArgs);
 
 static gemm_fn tile_fn(int tile, bool ta, bool tb, bool split)
 {
-#define PICK(BMN)                                                                          \
-    (ta ? (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, true, true, false>                     \
-              : (gemm_fn)gemm_tile_kernel<BMN, BMN, true, false, false>)                   \
-        : (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, false, true, false>                    \
-              : (gemm_fn)gemm_tile_kernel<BMN, BMN, false, false, false>))
-#define PICKS(BMN)                                                                         \
-    (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, false, true, true>                           \
-        : (gemm_fn)gemm_tile_kernel<BMN, BMN, false, false, true>)
+#define PICK(BMN, WGM, WGN)                                                                     \
+    (ta ? (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, WGM, WGN, true, true, false>                \
+              : (gemm_fn)gemm_tile_kernel<BMN, BMN, WGM, WGN, true, false, false>)              \
+        : (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, WGM, WGN, false, true, false>               \
+              : (gemm_fn)gemm_tile_kernel<BMN, BMN, WGM, WGN, false, false, false>))
+#define PICKS(BMN)                                                                              \
+    (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, 2, 2, false, true, true>                          \
+        : (gemm_fn)gemm_tile_kernel<BMN, BMN, 2, 2, false, false, true>)
     if (split) return tile == 64 ? PICKS(64) : PICKS(128);
     switch (tile) {
-    case 64: return PICK(64);
-    case 128: return PICK(128);
-    default: return PICK(256);
+    case 64: return PICK(64, 2, 2);
+    case 128: return PICK(128, 2, 2);
+    default: return PICK(256, 2, 4);
     }
 #undef PICK
 #undef PICKS
 }
 
+static int tile_threads(int variant) { return variant == 30 ? 512 : 256; }
+
 static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split)
 {
     switch (variant) {
-    case V_SKINNY8: return a32 ? (gemm_fn)gemm_skinny_kernel<8, true> : (gemm_fn)gemm_skinny_kernel<8, false>;
-    case V_SKINNY16: return a32 ? (gemm_fn)gemm_skinny_kernel<16, true> : (gemm_fn)gemm_skinny_kernel<16, false>;
-    case V_SKINNY32: return a32 ? (gemm_fn)gemm_skinny_kernel<32, true> : (gemm_fn)gemm_skinny_kernel<32, false>;
+    case V_SKINNY8:
+    case V_SKINNY16: return a32 ? (gemm_fn)gemm_skinny_kernel<1, SKINNY_NB, true> : (gemm_fn)gemm_skinny_kernel<1, SKINNY_NB, false>;
+    case V_SKINNY32: return a32 ? (gemm_fn)gemm_skinny_kernel<2, SKINNY_NB, true> : (gemm_fn)gemm_skinny_kernel<2, SKINNY_NB, false>;
     case V_TILE64: return tile_fn(64, ta, tb, split);
     case V_TILE128: return tile_fn(128, ta, tb, split);
     default: return tile_fn(256, ta, tb, split);
@@ -492,7 +497,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         if (M > 32 || !tb || ta) return fail(LITHOS_EINVAL, "gemm: the skinny kernel needs M <= 32, TRANS_B and no TRANS_A");
         if (a32 && (lda % 4)) return fail(LITHOS_EINVAL, "gemm: fp32 activations need lda %% 4 == 0");
         variant = M <= 8 ? V_SKINNY8 : M <= 16 ? V_SKINNY16 : V_SKINNY32;
-        plan->grid = {(uint32_t)((N + 15) / 16), 1, 1};
+        plan->grid = {(uint32_t)((N + 16 * SKINNY_NB - 1) / (16 * SKINNY_NB)), 1, 1};
     } else if (tile == 64 || tile == 128 || tile == 256) {
         if (split && tile == 256) return fail(LITHOS_EINVAL, "gemm: SPLIT_A is built for the 64 and 128 tiles only");
         variant = tile == 64 ? V_TILE64 : tile == 128 ? V_TILE128 : V_TILE256;
@@ -501,10 +506,10 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         return fail(LITHOS_EINVAL, "gemm: unknown tile selector %d", tile);
     }
     plan->total = plan->grid.x * plan->grid.y;
-    plan->threads = 256;
+    plan->threads = tile_threads(variant);
     plan->variant = variant;
     int occ = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void*)variant_fn(variant, ta, tb, a32, split), 256, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void*)variant_fn(variant, ta, tb, a32, split), tile_threads(variant), 0);
     plan->wg_per_cu = (e == hipSuccess && occ > 0) ? (uint32_t)occ : 1u;
     if (e != hipSuccess) (void)hipGetLastError();
     return LITHOS_OK;
@@ -525,7 +530,7 @@ int gemm_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     g.a_plane = op.dim[3]; g.c_plane = op.dim[4];
     gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B, op.flags & LITHOS_F_IN_F32,
                             op.flags & LITHOS_F_SPLIT_A);
-    LITHOS_HIP(launch_kernel(fn, dim3(atom.n), dim3(256), s, g, atom));
+    LITHOS_HIP(launch_kernel(fn, dim3(atom.n), dim3(plan.threads), s, g, atom));
     return LITHOS_OK;
 }
 

@@ -167,6 +167,83 @@ __global__ __launch_bounds__(256) void layernorm_kernel(RowArgs a, AtomArgs atom
     }
 }
 
+// Register-resident variant: the row is read ONCE with 16-byte (fp32) or
+// 8-byte (bf16) loads, four elements per thread and step, and stays in
+// registers for the mean, the centred variance and the output.  Needs
+// H % 4 == 0 and H <= 16 * TPR.
+template <bool IN32, bool OUT32, int TPR>
+__global__ __launch_bounds__(256) void layernorm_vec_kernel(RowArgs a, AtomArgs atom)
+{
+    __shared__ float red[4];
+    constexpr int NV = 4;                                   // 4-element groups per thread
+    const uint32_t L = atom_logical_block(atom);
+    constexpr int RPB = 256 / TPR;
+    const int64_t row = (int64_t)L * RPB + threadIdx.x / TPR;
+    const int t = threadIdx.x % TPR;
+    const bool live = row < a.rows;
+    const int64_t H = a.cols, off = row * H;
+    float v[NV][4];
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t c = 4 * (t + (int64_t)j * TPR);
+        v[j][0] = v[j][1] = v[j][2] = v[j][3] = 0.0f;
+        if (live && c < H) {
+            if constexpr (IN32) {
+                const float4 f = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.x) + off + c);
+                v[j][0] = f.x; v[j][1] = f.y; v[j][2] = f.z; v[j][3] = f.w;
+            } else {
+                const uint2 u = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.x) + off + c);
+                v[j][0] = __uint_as_float(u.x << 16); v[j][1] = __uint_as_float(u.x & 0xffff0000u);
+                v[j][2] = __uint_as_float(u.y << 16); v[j][3] = __uint_as_float(u.y & 0xffff0000u);
+            }
+            s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
+        }
+    }
+    const float mean = row_sum<TPR>(s, red) / (float)H;
+    float q = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t c = 4 * (t + (int64_t)j * TPR);
+        if (live && c < H)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { const float d = v[j][e] - mean; q += d * d; }
+    }
+    const float var = row_sum<TPR>(q, red) / (float)H;
+    const float rstd = 1.0f / sqrtf(var + a.f0);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t c = 4 * (t + (int64_t)j * TPR);
+        if (live && c < H) {
+            const float4 gm = *reinterpret_cast<const float4*>(a.p0 + c);
+            const float4 bt = *reinterpret_cast<const float4*>(a.p1 + c);
+            float y[4];
+            y[0] = (v[j][0] - mean) * rstd * gm.x + bt.x;
+            y[1] = (v[j][1] - mean) * rstd * gm.y + bt.y;
+            y[2] = (v[j][2] - mean) * rstd * gm.z + bt.z;
+            y[3] = (v[j][3] - mean) * rstd * gm.w + bt.w;
+            uint16_t hi[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) hi[e] = f32_to_bf16_bits(y[e]);
+            if constexpr (OUT32) {
+                *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + off + c) = make_float4(y[0], y[1], y[2], y[3]);
+                if (a.y2) {
+                    uint16_t* y2 = reinterpret_cast<uint16_t*>(a.y2);
+                    *reinterpret_cast<uint2*>(y2 + off + c) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+                    if (a.flags & LITHOS_F_OUT_SPLIT) {
+                        uint16_t lo[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) lo[e] = f32_to_bf16_bits(y[e] - bf16_bits_to_f32(hi[e]));
+                        *reinterpret_cast<uint2*>(y2 + a.rows * H + off + c) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+                    }
+                }
+            } else {
+                *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.y) + off + c) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+            }
+        }
+    }
+}
+
 // ---- RMSNorm ----------------------------------------------------------------
 template <bool IN32, bool OUT32, int TPR>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(RowArgs a, AtomArgs atom)
@@ -301,6 +378,9 @@ int rowops_plan(const lithos_op_t& op, OpPlan* plan)
         if (!op.in[1] || !op.in[2] || !op.out[0]) return fail(LITHOS_EINVAL, "layernorm: null gamma, beta or output");
         if (!(op.flags & LITHOS_F_OUT_F32) && op.out[1]) return fail(LITHOS_EINVAL, "layernorm: a bf16 copy needs OUT_F32");
         blocks = (rows + (256 / tpr_for(cols)) - 1) / (256 / tpr_for(cols));
+        if (cols % 4 == 0 && cols <= 16 * tpr_for(cols) && aligned16(op.in[0]) && aligned16(op.in[1]) && aligned16(op.in[2]) &&
+            aligned16(op.out[0]) && (!op.out[1] || aligned16(op.out[1])))
+            plan->variant = 1;
         break;
     case LITHOS_OP_RMSNORM:
         if (!op.in[1] || !op.out[0]) return fail(LITHOS_EINVAL, "rmsnorm: null weight or output");
@@ -352,7 +432,15 @@ int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& ato
         else      { if (out32) L2(silu_mul_kernel, false, true); else L2(silu_mul_kernel, false, false); }
         break;
     case LITHOS_OP_LAYERNORM:
-        if (tpr_for(a.cols) == 64) {
+        if (plan.variant == 1) {          // register-resident rows
+            if (tpr_for(a.cols) == 64) {
+                if (in32) { if (out32) L3(layernorm_vec_kernel, true, true, 64); else L3(layernorm_vec_kernel, true, false, 64); }
+                else      { if (out32) L3(layernorm_vec_kernel, false, true, 64); else L3(layernorm_vec_kernel, false, false, 64); }
+            } else {
+                if (in32) { if (out32) L3(layernorm_vec_kernel, true, true, 256); else L3(layernorm_vec_kernel, true, false, 256); }
+                else      { if (out32) L3(layernorm_vec_kernel, false, true, 256); else L3(layernorm_vec_kernel, false, false, 256); }
+            }
+        } else if (tpr_for(a.cols) == 64) {
             if (in32) { if (out32) L3(layernorm_kernel, true, true, 64); else L3(layernorm_kernel, true, false, 64); }
             else      { if (out32) L3(layernorm_kernel, false, true, 64); else L3(layernorm_kernel, false, false, 64); }
         } else {

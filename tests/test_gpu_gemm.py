@@ -112,7 +112,7 @@ def test_skinny_weight_streaming_gemm(m, n, k):
     a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=m, tb=True, dist="normal")
     ref = O.gemm(a_bits, b_bits, tb=True)
     c, grid, cnt = run_gemm(a_bits, b_bits, m, n, k, tb=True, tile=B.TILE_SKINNY, count=True)
-    assert grid == ((n + 15) // 16, 1, 1)
+    assert grid == ((n + 31) // 32, 1, 1)
     assert cnt.cpu().tolist() == [1] * grid[0]
     assert not torch.isnan(c).any()
     assert rel_fro(c, ref) <= FRO_TOL
