@@ -1,22 +1,32 @@
 #!/usr/bin/env python3
 """Two-tenant stacking benchmark on one MI355X.
 
-Workload: a high-priority tenant serves a 6-layer MLP (batch 8, hidden 4096,
-GEMM+bias+GELU+LayerNorm per layer) under Poisson arrivals at 200 requests/s
-on a 64-CU quota; a best-effort tenant runs back-to-back bf16 8192^3 GEMMs on a
-192-CU quota and steals the idle high-priority CUs at atom boundaries.
+Default workload (cfg2): a high-priority tenant serves a 6-layer MLP (batch 8,
+hidden 4096, GEMM+bias+GELU+LayerNorm per layer) under Poisson arrivals at 200
+requests/s on a 64-CU quota; a best-effort tenant runs back-to-back bf16 8192^3
+GEMMs on a 192-CU quota and steals the idle high-priority CUs at atom
+boundaries.
 
 A "step" is one high-priority request served while the best-effort tenant
 runs.  The timed region is exactly --steps requests after --warmup requests.
 One JSON line is printed: value = high-priority p99 latency (ms), with the
 aggregate throughput, the atom overhead, the comparators (high-priority alone,
-best-effort alone, unpartitioned co-execution), the roofline of the dominant
-kernel (the best-effort GEMM) and the CPU oracle timed beside it.
+best-effort alone, unpartitioned co-execution, static masks, masks+stealing),
+the roofline of the dominant kernel (the best-effort GEMM) and the CPU oracle
+timed beside it.
+
+Other workloads (same JSON layout, not the headline):
+  --workload cfg3   encoder inference (12 layers, hidden 768, seq 128, --batch) stacked with
+                    training-shaped GEMMs (24-layer hidden-1024 FFN-4096 block, 16384 tokens)
+  --workload cfg5   decoder-layer decode (32 layers, hidden 4096, GQA 32/8, FFN 14336, KV 2048,
+                    --batch) stacked with the cfg2 best-effort GEMM
+  --workload cfg4   right-sizing sweep over every kernel of cfg3 (CU counts 8..256 step 8)
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -27,21 +37,177 @@ if ROOT not in sys.path:
 
 METRIC = "high-priority p99 latency + aggregate tput under 2-tenant stacking; atom overhead %"
 MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16
-RATE = 200.0                         # requests per second (Poisson)
-BE_N = 8192
-BE_TILE = 128
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per whole 8192^3 launch of the 256x256-tile GEMM, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# scaled by the 1 GiB copy calibration (profiles/): filled in by measurement, None until measured.
+TRAFFIC_BYTES = {256: None, 128: 3.36e9}
 
 
-def p99(x):
+def nearest_rank(x, q):
     import numpy as np
     s = np.sort(np.asarray(x))
-    return float(s[max(0, int(np.ceil(0.99 * len(s))) - 1)])      # nearest rank
+    return float(s[max(0, int(math.ceil(q * len(s))) - 1)])
 
 
-def pct(x, q):
-    import numpy as np
-    s = np.sort(np.asarray(x))
-    return float(s[max(0, int(np.ceil(q * len(s))) - 1)])
+# ---------------------------------------------------------------------------------------------
+# workloads: each builds device-resident inputs and returns operator lists
+# ---------------------------------------------------------------------------------------------
+
+def be_gemm_8192(B, inputs, torch, tile):
+    n = 8192
+    a_bits, b_bits = inputs.gemm_operands(n, n, n, seed=4)
+    a, b = inputs.bits_to_torch(a_bits, "cuda").contiguous(), inputs.bits_to_torch(b_bits, "cuda").contiguous()
+    c = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
+    op = B.gemm_op(a, b, c, n, n, n, tile=tile)
+    desc = "gemm_tile_kernel<%d,%d> 8192^3 bf16, whole launch, 256 CUs" % (tile, tile)
+    return dict(ops=[op], flop=2.0 * n ** 3, dominant=(op, 2.0 * n ** 3, desc), host=(a_bits, b_bits),
+                text="bf16 8192^3 GEMMs back to back")
+
+
+def wl_cfg2(args, B, inputs, torch):
+    from paper_2504_15465_amd.models import MlpChain
+    layers = inputs.mlp_params(6, 4096, seed=1)
+    pool_bits = inputs.mlp_requests(pool=64, batch=8, hidden=4096, seed=2)
+    chain = MlpChain(layers, 8, "cuda")
+    pool = [inputs.bits_to_torch(pool_bits[i], "cuda").contiguous() for i in range(64)]
+    be = be_gemm_8192(B, inputs, torch, args.be_tile)
+
+    def cpu_baseline():
+        from oracle import models as OM
+        from oracle import ops as O
+        t0 = time.perf_counter()
+        OM.mlp_forward(pool_bits[0], layers)
+        hp_ms = (time.perf_counter() - t0) * 1e3
+        rows = 32
+        t0 = time.perf_counter()
+        O.gemm(be["host"][0][:rows], be["host"][1])
+        be_s = time.perf_counter() - t0
+        return {"value": hp_ms, "unit": "ms", "cores": O.num_threads(), "kind": "oracle",
+                "sample": "1 high-priority request (6 layers, batch 8) = value (no queueing, no tenants); plus %d of "
+                          "8192 rows of one 8192^3 best-effort GEMM" % rows,
+                "be_gemm_tflops": 2.0 * rows * 8192 * 8192 / be_s * 1e-12}
+
+    return dict(name="cfg2: HP 6-layer MLP batch 8 hidden 4096 Poisson 200 req/s on 64 CUs + BE bf16 8192^3 GEMMs "
+                     "on 192 CUs, idle-CU stealing, atomized",
+                hp_requests=[chain.ops(x) for x in pool], rate=200.0, be=be, cpu_baseline=cpu_baseline, keep=[chain, pool])
+
+
+def training_block_ops(B, inputs, torch, n_layers=24, hidden=1024, ffn=4096, tokens=16384):
+    """Forward and backward GEMMs (Y = XW, dX = dY W^T, dW = X^T dY) of a transformer block stack."""
+    dev, bf = "cuda", torch.bfloat16
+    shapes = [("qkv", hidden, 3 * hidden), ("out", hidden, hidden), ("ffn1", hidden, ffn), ("ffn2", ffn, hidden)]
+    x = {k: inputs.bits_to_torch(inputs.normal_bits((tokens, k), [12, k]), dev) for k in {s[1] for s in shapes}}
+    dy = {n: inputs.bits_to_torch(inputs.normal_bits((tokens, n), [13, n]), dev) for n in {s[2] for s in shapes}}
+    y = {n: torch.empty((tokens, n), dtype=bf, device=dev) for n in {s[2] for s in shapes}}
+    dx = {k: torch.empty((tokens, k), dtype=bf, device=dev) for k in {s[1] for s in shapes}}
+    ops, flop, keep, distinct = [], 0.0, [x, dy, y, dx], {}
+    for layer in range(n_layers):
+        for name, k, n in shapes:
+            w = inputs.bits_to_torch(inputs.normal_bits((k, n), [14, layer, k, n], 0.02), dev)
+            dw = torch.empty((k, n), dtype=bf, device=dev)
+            keep += [w, dw]
+            trio = [B.gemm_op(x[k], w, y[n], tokens, n, k),                       # Y  = X W
+                    B.gemm_op(dy[n], w, dx[k], tokens, k, n, tb=True),            # dX = dY W^T
+                    B.gemm_op(x[k], dy[n], dw, k, n, tokens, ta=True)]            # dW = X^T dY
+            ops += trio
+            flop += 3 * 2.0 * tokens * k * n
+            if layer == 0:
+                for kind, o in zip(("fwd", "dX", "dW"), trio):
+                    distinct["be_%s_%s" % (name, kind)] = (o, 2.0 * tokens * k * n)
+    return ops, flop, keep, distinct
+
+
+def wl_cfg3(args, B, inputs, torch):
+    from paper_2504_15465_amd.models import EncoderChain
+    b = args.batch
+    layers = inputs.encoder_params(12, 768, 3072, seed=10)
+    chain = EncoderChain(layers, b, 128, 12)
+    x = inputs.encoder_hidden(b, 128, 768, seed=11)
+    chain.set_input(x)
+    ops, flop, keep, distinct = training_block_ops(B, inputs, torch)
+    dom = distinct["be_ffn1_fwd"]
+    be = dict(ops=ops, flop=flop, dominant=(dom[0], dom[1], "gemm_tile_kernel 16384x4096x1024 bf16 (FFN1 forward), whole launch, 256 CUs"),
+              text="fwd + dX + dW GEMMs of a 24-layer hidden-1024 FFN-4096 block over 16384 tokens (288 GEMMs per iteration)")
+
+    def cpu_baseline():
+        from oracle import models as OM
+        from oracle import ops as O
+        t0 = time.perf_counter()
+        OM.encoder_forward(x[:128] if b > 1 else x, layers, 1, 128, 12)
+        return {"value": (time.perf_counter() - t0) * 1e3, "unit": "ms", "cores": O.num_threads(), "kind": "oracle",
+                "sample": "1 high-priority request at batch 1 (12 layers, 128 tokens)"}
+
+    return dict(name="cfg3: HP 12-layer encoder hidden 768 12 heads seq 128 batch %d, Poisson at 80%% of its 64-CU "
+                     "service rate + BE training-shaped GEMMs (24 layers, hidden 1024, FFN 4096, 16384 tokens)" % b,
+                hp_requests=[chain.ops()], rate=None, be=be, cpu_baseline=cpu_baseline, keep=[chain, keep],
+                distinct=distinct, chain=chain)
+
+
+def wl_cfg5(args, B, inputs, torch):
+    from paper_2504_15465_amd.models import DecoderChain
+    b, n_layers = args.batch, args.layers
+    H, n_q, n_kv, F, pos = 4096, 32, 8, 14336, 2048
+    layers = inputs.decoder_params(n_layers, H, n_q, n_kv, F, seed=20)
+    ks, vs = inputs.decoder_kv_cache(n_layers, b, pos, n_kv, H // n_q, seed=21)
+    chain = DecoderChain(layers, ks, vs, b, n_q, n_kv, pos)
+    x = inputs.decoder_hidden(b, H, seed=22)
+    chain.set_input(x)
+    be = be_gemm_8192(B, inputs, torch, args.be_tile)
+
+    def cpu_baseline():
+        from oracle import models as OM
+        from oracle import ops as O
+        t0 = time.perf_counter()
+        OM.decoder_decode_step(x[:1], layers[:1], [ks[0][:1]], [vs[0][:1]], n_q, n_kv, pos)
+        return {"value": (time.perf_counter() - t0) * 1e3 * n_layers, "unit": "ms", "cores": O.num_threads(), "kind": "oracle",
+                "sample": "1 decoder layer at batch 1, scaled by %d layers" % n_layers}
+
+    return dict(name="cfg5: HP %d-layer decoder decode step hidden 4096 GQA 32/8 FFN 14336 KV 2048 batch %d, Poisson at "
+                     "80%% of its 64-CU service rate + BE bf16 8192^3 GEMMs" % (n_layers, b),
+                hp_requests=[chain.ops()], rate=None, be=be, cpu_baseline=cpu_baseline, keep=[chain])
+
+
+# ---------------------------------------------------------------------------------------------
+# stacking legs
+# ---------------------------------------------------------------------------------------------
+
+def make_world(B, cfg, masks=True):
+    ctx = B.lithos_init(0, cfg)
+    if not masks:
+        return ctx, [], B.lithos_tenant_create(ctx, B.CLASS_HP, None), B.lithos_tenant_create(ctx, B.CLASS_BE, None)
+    p_hp = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 64, B.MASK_STRIPED, 0))
+    p_be = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 192, B.MASK_STRIPED, 64))
+    return ctx, [p_hp, p_be], B.lithos_tenant_create(ctx, B.CLASS_HP, p_hp), B.lithos_tenant_create(ctx, B.CLASS_BE, p_be)
+
+
+def drop_world(B, ctx, parts, tenants):
+    for t in tenants:
+        if t is not None:
+            B.lithos_tenant_destroy(t)
+    for p in parts:
+        B.lithos_destroy_partition(p)
+    B.lithos_shutdown(ctx)
+
+
+def stacked_leg(B, torch, wl, t_hp, t_be, arrivals, warm):
+    """HP open loop (first `warm` requests untimed) against the BE closed loop."""
+    drv = B.lithos_drive_closed_loop_start(t_be, wl["be"]["ops"], depth=2) if t_be is not None else None
+    if drv is not None:
+        time.sleep(0.2)
+    if warm > 0:
+        B.lithos_drive_open_loop(t_hp, wl["hp_requests"], arrivals[:warm])
+    arr = arrivals[warm:] - (arrivals[warm - 1] if warm > 0 else 0.0)
+    s0 = B.lithos_tenant_stats(t_be) if t_be is not None else None
+    torch.cuda.synchronize() if drv is None else None
+    t0 = time.perf_counter()
+    lat = B.lithos_drive_open_loop(t_hp, wl["hp_requests"], arr)
+    B.lithos_sync(t_hp)
+    wall = time.perf_counter() - t0
+    s1 = B.lithos_tenant_stats(t_be) if t_be is not None else None
+    iters, secs = (0, 1.0)
+    if drv is not None:
+        iters, secs = B.lithos_drive_closed_loop_stop(drv)
+    return dict(lat=lat, wall=wall, be_iters=iters, be_secs=secs, s0=s0, s1=s1)
 
 
 def main():
@@ -49,8 +215,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3000)
     ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--batch", type=int, default=8, help="cfg3/cfg5 high-priority batch size")
+    ap.add_argument("--layers", type=int, default=32, help="cfg5 decoder layers")
     ap.add_argument("--atom-us", type=float, default=250.0)
-    ap.add_argument("--max-outstanding", type=int, default=2)
+    ap.add_argument("--max-outstanding", type=int, default=1)
+    ap.add_argument("--be-tile", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     args = ap.parse_args()
@@ -62,187 +232,109 @@ def main():
     import torch
     from paper_2504_15465_amd import binding as B
     from paper_2504_15465_amd import inputs
-    from paper_2504_15465_amd.models import MlpChain
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = "cuda"
+    if args.workload == "cfg4":
+        return rightsize_sweep(args, B, inputs, torch)
     K, W = args.steps, args.warmup
-
-    # ---- synthetic, seeded inputs (resident in HBM before any timed region) ----
-    layers = inputs.mlp_params(6, 4096, seed=1)
-    pool_bits = inputs.mlp_requests(pool=64, batch=8, hidden=4096, seed=2)
-    chain = MlpChain(layers, 8, dev)
-    pool = [inputs.bits_to_torch(pool_bits[i], dev).contiguous() for i in range(64)]
-    a_bits, b_bits = inputs.gemm_operands(BE_N, BE_N, BE_N, seed=4)
-    a_be, b_be = inputs.bits_to_torch(a_bits, dev).contiguous(), inputs.bits_to_torch(b_bits, dev).contiguous()
-    c_be = torch.empty((BE_N, BE_N), dtype=torch.bfloat16, device=dev)
-    arrivals = inputs.poisson_arrivals(RATE, W + K, seed=3)
+    wl = {"cfg2": wl_cfg2, "cfg3": wl_cfg3, "cfg5": wl_cfg5}[args.workload](args, B, inputs, torch)
     torch.cuda.synchronize()
-    be_flop = 2.0 * BE_N ** 3
-    hp_flop = 6 * 2.0 * 8 * 4096 * 4096
 
-    def be_op():
-        return B.gemm_op(a_be, b_be, c_be, BE_N, BE_N, BE_N, tile=BE_TILE)
+    def sched_cfg(steal, atomize):
+        return B.Config.default(atom_duration_us=args.atom_us, max_outstanding=args.max_outstanding,
+                                max_outstanding_hp=64, steal=steal, atomize=atomize)
 
-    def hp_requests():
-        return [chain.ops(x) for x in pool]
+    # offered load: fixed for cfg2; else 80 % of the solo service rate on the 64-CU quota (Section 7.1 rule)
+    rate = wl["rate"]
+    if rate is None:
+        ctx, parts, t_hp, t_be = make_world(B, sched_cfg(0, 0))
+        ops = wl["hp_requests"][0]
+        for rep in range(3):
+            t0 = time.perf_counter()
+            for _ in range(10):
+                for op in ops:
+                    B.lithos_submit(t_hp, op)
+                B.lithos_sync(t_hp)
+            solo = (time.perf_counter() - t0) / 10
+        drop_world(B, ctx, parts, [t_hp, t_be])
+        rate = 0.8 / solo
+    arrivals = inputs.poisson_arrivals(rate, W + K, seed=3)
 
-    def run_pair(ctx, t_hp, t_be, n_req, arr):
-        """HP open loop + BE closed loop; returns (latencies_us, be_iters, be_seconds, wall_s)."""
-        drv = B.lithos_drive_closed_loop_start(t_be, [be_op()], depth=2) if t_be is not None else None
-        if drv is not None:
-            time.sleep(0.2)                      # let the best-effort tenant reach steady state
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        lat = B.lithos_drive_open_loop(t_hp, hp_requests(), arr) if t_hp is not None else None
-        if t_hp is None:
-            time.sleep(arr)
-        torch.cuda.synchronize() if drv is None else None
-        wall = time.perf_counter() - t0
-        iters, secs = (0, 0.0)
-        if drv is not None:
-            iters, secs = B.lithos_drive_closed_loop_stop(drv)
-        return lat, iters, secs, wall
+    def summarise(r, skip=0):
+        lat = r["lat"][skip:]
+        return {"p50_us": nearest_rank(lat, 0.5), "p99_us": nearest_rank(lat, 0.99),
+                "be_tflops": r["be_iters"] * wl["be"]["flop"] / r["be_secs"] * 1e-12}
 
-    out = {}
-
-    # ---- comparators -------------------------------------------------------------
     comp = {}
     if not args.no_comparators:
-        n_c = min(K, 1000)
-        arr_c = arrivals[: n_c + 100] - 0.0
-        # (i) high-priority alone on the whole GPU ("ideal")
-        ctx = B.lithos_init(0, None)
-        t = B.lithos_tenant_create(ctx, B.CLASS_HP, None)
-        lat, _, _, _ = run_pair(ctx, t, None, 0, arr_c)
-        B.lithos_tenant_destroy(t)
-        comp["hp_alone_full_gpu"] = {"p50_us": pct(lat[100:], 0.5), "p99_us": p99(lat[100:])}
-        # (ii) best-effort alone on the whole GPU
-        t = B.lithos_tenant_create(ctx, B.CLASS_BE, None)
-        _, iters, secs, _ = run_pair(ctx, None, t, 0, 2.0)
-        B.lithos_tenant_destroy(t)
-        comp["be_alone_full_gpu"] = {"gemms_per_s": iters / secs, "tflops": iters * be_flop / secs * 1e-12}
+        n_c = min(K, 1000) + 100
+        arr_c = arrivals[:n_c]
+        # (i) high-priority alone on the whole GPU ("ideal"), (ii) best-effort alone
+        ctx, parts, t_hp, t_be = make_world(B, None, masks=False)
+        r = stacked_leg(B, torch, wl, t_hp, None, arr_c, 100)
+        comp["hp_alone_full_gpu"] = {k: v for k, v in summarise(r).items() if k != "be_tflops"}
+        drv = B.lithos_drive_closed_loop_start(t_be, wl["be"]["ops"], depth=2)
+        time.sleep(2.0)
+        iters, secs = B.lithos_drive_closed_loop_stop(drv)
+        comp["be_alone_full_gpu"] = {"iterations_per_s": iters / secs, "tflops": iters * wl["be"]["flop"] / secs * 1e-12}
         # (iii) unpartitioned co-execution: two plain queues, no masks, no atoms
-        t1 = B.lithos_tenant_create(ctx, B.CLASS_HP, None)
-        t2 = B.lithos_tenant_create(ctx, B.CLASS_BE, None)
-        lat, iters, secs, _ = run_pair(ctx, t1, t2, 0, arr_c)
-        B.lithos_tenant_destroy(t1)
-        B.lithos_tenant_destroy(t2)
-        comp["unpartitioned_coexecution"] = {"p50_us": pct(lat[100:], 0.5), "p99_us": p99(lat[100:]),
-                                             "be_tflops": iters * be_flop / secs * 1e-12}
-        B.lithos_shutdown(ctx)
+        comp["unpartitioned_coexecution"] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr_c, 100))
+        drop_world(B, ctx, parts, [t_hp, t_be])
+        # (iv) static masks, (v) masks + stealing, both without atoms
+        for name, steal in (("static_masks", 0), ("masks_stealing", 1)):
+            ctx, parts, t_hp, t_be = make_world(B, sched_cfg(steal, 0))
+            comp[name] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr_c, 100))
+            drop_world(B, ctx, parts, [t_hp, t_be])
 
-        # (iv)/(v) static masks without / with stealing, no atoms
-        for name, steal, atomize in (("static_masks", 0, 0), ("masks_stealing", 1, 0)):
-            cfg = B.Config.default(atom_duration_us=args.atom_us, max_outstanding=args.max_outstanding,
-                                   max_outstanding_hp=32, steal=steal, atomize=atomize)
-            ctx = B.lithos_init(0, cfg)
-            p_hp = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 64, B.MASK_STRIPED, 0))
-            p_be = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 192, B.MASK_STRIPED, 64))
-            t1 = B.lithos_tenant_create(ctx, B.CLASS_HP, p_hp)
-            t2 = B.lithos_tenant_create(ctx, B.CLASS_BE, p_be)
-            lat, iters, secs, _ = run_pair(ctx, t1, t2, 0, arr_c)
-            B.lithos_tenant_destroy(t1)
-            B.lithos_tenant_destroy(t2)
-            B.lithos_destroy_partition(p_hp)
-            B.lithos_destroy_partition(p_be)
-            B.lithos_shutdown(ctx)
-            comp[name] = {"p50_us": pct(lat[100:], 0.5), "p99_us": p99(lat[100:]),
-                          "be_tflops": iters * be_flop / secs * 1e-12}
-    out["comparators"] = comp
-
-    # ---- main leg: quotas 64/192, stealing, atomization ----------------------------
-    cfg = B.Config.default(atom_duration_us=args.atom_us, max_outstanding=args.max_outstanding,
-                           max_outstanding_hp=32, steal=1, atomize=1)
-    ctx = B.lithos_init(0, cfg)
-    p_hp = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 64, B.MASK_STRIPED, 0))
-    p_be = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 192, B.MASK_STRIPED, 64))
-    p_all = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 256, B.MASK_STRIPED, 0))
-    t_hp = B.lithos_tenant_create(ctx, B.CLASS_HP, p_hp)
-    t_be = B.lithos_tenant_create(ctx, B.CLASS_BE, p_be)
-    drv = B.lithos_drive_closed_loop_start(t_be, [be_op()], depth=2)
-    time.sleep(0.2)
-    reqs = hp_requests()
-    if W > 0:
-        B.lithos_drive_open_loop(t_hp, reqs, arrivals[:W])          # untimed warm-up requests
-    arr_k = arrivals[W:W + K] - (arrivals[W - 1] if W > 0 else 0.0)
-    s0 = B.lithos_tenant_stats(t_be)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    lat = B.lithos_drive_open_loop(t_hp, reqs, arr_k)               # exactly K timed steps
-    B.lithos_sync(t_hp)
-    wall = time.perf_counter() - t0
-    s1 = B.lithos_tenant_stats(t_be)
-    iters, secs = B.lithos_drive_closed_loop_stop(drv)
-    torch.cuda.synchronize()
+    # ---- main leg: quotas 64/192, stealing, atomization --------------------------------------------
+    ctx, parts, t_hp, t_be = make_world(B, sched_cfg(1, 1))
+    r = stacked_leg(B, torch, wl, t_hp, t_be, arrivals, W)          # exactly K timed steps after W warm-up
     s_hp = B.lithos_tenant_stats(t_hp)
-    be_tflops = iters * be_flop / secs * 1e-12
-    hp_p99_us, hp_p50_us = p99(lat), pct(lat, 0.5)
+    s0, s1 = r["s0"], r["s1"]
+    main_sum = summarise(r)
 
-    # ---- atom overhead and roofline of the dominant kernel (device time stamps) -----
-    op = be_op()
+    # ---- atom overhead and roofline of the dominant kernel (device time stamps on its queue) -------
+    p_all = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 256, B.MASK_STRIPED, 0))
+    op, flop, desc = wl["be"]["dominant"]
     grid, wg_per_cu = B.lithos_op_grid(ctx, op)
     total_blocks = grid[0] * grid[1]
     whole_mean, whole_med = B.lithos_time_launch(ctx, op, 0, p_all, 3, 20)
     atoms_per_kernel = max(1.0, (s1.atoms - s0.atoms) / max(1, (s1.kernels - s0.kernels)))
-    atom_blocks = int(np.ceil(total_blocks / atoms_per_kernel))
     quantum = 256 * wg_per_cu
-    atom_blocks = min(total_blocks, -(-atom_blocks // quantum) * quantum)
+    atom_blocks = min(total_blocks, -(-int(math.ceil(total_blocks / atoms_per_kernel)) // quantum) * quantum)
     at_mean, at_med = B.lithos_time_launch(ctx, op, atom_blocks, p_all, 3, 20)
     overhead_pct = (at_med - whole_med) / whole_med * 100.0
-    achieved = be_flop / (whole_mean * 1e-6) * 1e-12
+    achieved = flop / (whole_mean * 1e-6) * 1e-12
+    drop_world(B, ctx, parts + [p_all], [t_hp, t_be])
 
-    B.lithos_tenant_destroy(t_hp)
-    B.lithos_tenant_destroy(t_be)
-    for p in (p_hp, p_be, p_all):
-        B.lithos_destroy_partition(p)
-    B.lithos_shutdown(ctx)
-
-    # ---- CPU oracle on the host cores, bounded sample ---------------------------------
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import models as OM
-        from oracle import ops as O
-        t0 = time.perf_counter()
-        OM.mlp_forward(pool_bits[0], layers)
-        hp_ms = (time.perf_counter() - t0) * 1e3
-        rows = 32
-        t0 = time.perf_counter()
-        O.gemm(a_bits[:rows], b_bits)
-        be_s = time.perf_counter() - t0
-        cpu = {"value": hp_ms, "unit": "ms", "cores": O.num_threads(), "kind": "oracle",
-               "sample": "1 high-priority request (6 layers, batch 8) = value; plus %d of %d rows of one 8192^3 "
-                         "best-effort GEMM" % (rows, BE_N),
-               "be_gemm_tflops": 2.0 * rows * BE_N * BE_N / be_s * 1e-12}
+    cpu = None if args.no_cpu_baseline else wl["cpu_baseline"]()
 
     ideal = comp.get("hp_alone_full_gpu", {}).get("p99_us")
     be_alone = comp.get("be_alone_full_gpu", {}).get("tflops")
-    hp_served = K / wall
-    agg = None
-    if be_alone:
-        agg = min(1.0, hp_served / RATE) + be_tflops / be_alone       # Section 7.1: HP / load + BE / BE-alone
+    hp_served = K / r["wall"]
+    agg = (min(1.0, hp_served / rate) + main_sum["be_tflops"] / be_alone) if be_alone else None
+    traffic = TRAFFIC_BYTES.get(args.be_tile) if args.workload in ("cfg2", "cfg5") else None
     line = {
         "metric": METRIC,
-        "value": hp_p99_us * 1e-3,
+        "value": main_sum["p99_us"] * 1e-3,
         "unit": "ms",
         "n_gpus": 1,
         "steps": K,
         "warmup": W,
-        "ms_per_step": wall / K * 1e3,
+        "ms_per_step": r["wall"] / K * 1e3,
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "cfg2: HP 6-layer MLP batch 8 hidden 4096 Poisson 200 req/s on 64 CUs + BE bf16 "
-                               "8192^3 GEMMs on 192 CUs, idle-CU stealing, atomized",
-                   "atom_duration_us": args.atom_us, "max_outstanding": args.max_outstanding,
-                   "be_gemm_tile": BE_TILE, "cu_split": "64/192"},
-        "hp_p50_ms": hp_p50_us * 1e-3,
-        "hp_p99_ms": hp_p99_us * 1e-3,
-        "hp_p99_over_ideal": (hp_p99_us / ideal) if ideal else None,
+        "config": {"workload": wl["name"], "offered_load_per_s": rate, "atom_duration_us": args.atom_us,
+                   "max_outstanding": args.max_outstanding, "be_gemm_tile": args.be_tile, "cu_split": "64/192"},
+        "hp_p50_ms": main_sum["p50_us"] * 1e-3,
+        "hp_p99_ms": main_sum["p99_us"] * 1e-3,
+        "hp_p99_over_ideal": (main_sum["p99_us"] / ideal) if ideal else None,
+        "hp_p99_vs_unpartitioned": (comp["unpartitioned_coexecution"]["p99_us"] / main_sum["p99_us"]) if comp else None,
         "hp_served_per_s": hp_served,
-        "be_tflops": be_tflops,
+        "be_tflops": main_sum["be_tflops"],
         "aggregate_throughput_normalised": agg,
         "atom_overhead_pct": overhead_pct,
         "atom_overhead_detail": {"atom_blocks": atom_blocks, "total_blocks": total_blocks,
@@ -252,15 +344,63 @@ def main():
                       "be_mispredict_rate": (s1.mispredicts / s1.predictions) if s1.predictions else None,
                       "hp_mispredict_rate": (s_hp.mispredicts / s_hp.predictions) if s_hp.predictions else None},
         "comparators": comp,
-        "roofline": {"bound": "mfma", "kernel": "gemm_tile_kernel<%d,%d> 8192^3 bf16, whole launch, 256 CUs" % (BE_TILE, BE_TILE),
-                     "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "launch_us": whole_mean, "flop_per_launch": be_flop},
+        "roofline": {"bound": "mfma", "kernel": desc, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                     "launch_us": whole_mean, "flop_per_launch": flop},
         "cpu_baseline": cpu,
         "paper_context": "LithOS on A100 (its NVIDIA hardware): 13x lower P99 than MPS, 3x lower tail and 1.6x "
                          "aggregate throughput vs best prior system; atomization cost 10% BE throughput",
     }
     print(json.dumps(line))
+
+
+# ---------------------------------------------------------------------------------------------
+# cfg4: right-sizing sweep over every kernel of cfg3
+# ---------------------------------------------------------------------------------------------
+
+def rightsize_sweep(args, B, inputs, torch):
+    import numpy as np
+    wl = wl_cfg3(args, B, inputs, torch)
+    torch.cuda.synchronize()
+    ctx = B.lithos_init(0, None)
+    kernels = {}
+    names = {B.OP_GEMM: "gemm", B.OP_ATTN_ENC: "attention", B.OP_LAYERNORM: "layernorm", B.OP_BIAS_ACT: "cast"}
+    layer_ops = wl["hp_requests"][0][2:9]             # one encoder layer (the 12 layers repeat these shapes)
+    for i, o in enumerate(layer_ops):
+        kernels["hp_%d_%s" % (i, names.get(o.kind, str(o.kind)))] = (o, 12)
+    for k, (o, _) in wl["distinct"].items():
+        kernels[k] = (o, 24)
+    rows, full_cs, chosen_cs = [], 0.0, 0.0
+    t_full, t_chosen, cu_time = 0.0, 0.0, 0.0
+    for name, (o, count) in kernels.items():
+        r = B.lithos_rightsize(ctx, o, 8, 256, 8, 5, 50, 0.04)
+        cus = list(r.cus[: r.n_points])
+        lat = list(r.median_us[: r.n_points])
+        # R^2 of the two-point model over the sweep
+        pred = [r.model_m / c + r.model_b for c in cus]
+        mean = sum(lat) / len(lat)
+        ss_tot = sum((v - mean) ** 2 for v in lat)
+        r2 = 1.0 - sum((a - b) ** 2 for a, b in zip(lat, pred)) / ss_tot if ss_tot > 0 else 1.0
+        rows.append({"kernel": name, "launches_per_pass": count, "full_us": r.full_us, "chosen_cus": r.chosen_cus,
+                     "chosen_us": r.chosen_us, "occupancy_bound_cus": r.occupancy_bound_cus,
+                     "model_cus": r.model_cus, "model_r2": r2, "curve_us": [round(v, 2) for v in lat]})
+        t_full += count * r.full_us
+        t_chosen += count * r.chosen_us
+        cu_time += count * r.chosen_us * r.chosen_cus
+        full_cs += count * 256 * r.full_us
+        chosen_cs += count * r.chosen_cus * r.chosen_us
+    B.lithos_shutdown(ctx)
+    out = {"metric": "right-sizing sweep (cfg4): CU-seconds saved and end-to-end slowdown at 4 % per-kernel slip",
+           "value": 1.0 - (cu_time / t_chosen) / 256.0, "unit": "fraction of CUs saved (time-weighted)",
+           "n_gpus": 1, "higher_is_better": True, "data": "synthetic", "dtype": "bf16",
+           "config": {"workload": "cfg4: every kernel of cfg3 (encoder layer at batch %d, training GEMMs), CUs 8..256 step 8, "
+                                  "5 warm + 50 timed launches, median" % args.batch, "slowdown": 0.04},
+           "cu_seconds_saved_per_pass": (full_cs - chosen_cs) * 1e-6,
+           "predicted_end_to_end_slowdown": t_chosen / t_full - 1.0,
+           "time_weighted_model_r2": sum(k["model_r2"] * k["launches_per_pass"] * k["full_us"] for k in rows) / t_full,
+           "kernels": rows,
+           "paper_context": "LithOS on A100: capacity savings up to 51 %, mean 26 %, at latency slip 1.1; R^2 0.92-0.99"}
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":

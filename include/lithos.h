@@ -153,8 +153,22 @@ int lithos_create_partition(lithos_ctx_t* ctx, const uint32_t* cu_mask, uint32_t
                             lithos_partition_t** out);
 int lithos_destroy_partition(lithos_partition_t* p);
 int lithos_partition_cus(const lithos_partition_t* p, int* n_cus_out);
-/* the partition's HIP stream, as a hipStream_t (for event timing by the caller) */
+/* the partition's HIP stream, as a hipStream_t (for event timing by the caller).
+ * lithos_tenant_create may replace it (see lithos_partitions_coupled): ask again
+ * after tenants have been created. */
 int lithos_partition_stream(const lithos_partition_t* p, void** stream_out);
+
+/* Do the two partitions' queues share a command-processor pipe?  Measured: a grid
+ * with more workgroups than `busy`'s CUs hold at once is started on `busy`, then a
+ * one-block kernel on `probe`; *coupled_out = 1 if the latter had to wait for the
+ * grid to be dispatched.  Both queues must be idle.  Coupled queues are legal but
+ * delay each other by whole kernels; lithos_tenant_create replaces a quota
+ * partition's queue (same mask) until it is independent of the other tenants'.
+ * A queue's pipe follows from its position among the process's live queues, so
+ * queues retired while tenants exist are kept until the last tenant is destroyed;
+ * queues that other code in the process destroys can still move ours. */
+int lithos_partitions_coupled(lithos_ctx_t* ctx, const lithos_partition_t* busy, const lithos_partition_t* probe,
+                              int* coupled_out);
 
 /* Run `n_wg` probe workgroups on the partition; xcd_out/cu_out[n_wg] receive
  * the die and the (shader-engine, array, CU) hardware id each one ran on. */
@@ -233,7 +247,10 @@ typedef struct lithos_stats {
 } lithos_stats_t;
 
 /* quota: the partition whose CUs the tenant is guaranteed.  Quotas of
- * different tenants must be disjoint.  quota NULL makes a pass-through tenant:
+ * different tenants must be disjoint.  Call while the context's queues are idle:
+ * the partition's queue may be re-created (same CU mask) so that it does not share
+ * a command-processor pipe with another tenant's queue, and the queues for
+ * quota + stolen CUs of each pair of tenants are created here.  quota NULL makes a pass-through tenant:
  * every kernel is launched whole, at submission, on an unmasked queue of the
  * tenant's own (the unpartitioned co-execution that the scheduler is compared
  * with). */

@@ -77,7 +77,7 @@ class CoreAtom(C.Structure):
 EXPORTS = [
     "lithos_init", "lithos_shutdown", "lithos_device_info", "lithos_last_error",
     "lithos_make_mask", "lithos_create_partition", "lithos_destroy_partition", "lithos_partition_cus",
-    "lithos_partition_stream", "lithos_probe_partition",
+    "lithos_partition_stream", "lithos_probe_partition", "lithos_partitions_coupled",
     "lithos_op_grid", "lithos_launch_atomized", "lithos_launch_atom", "lithos_partition_sync",
     "lithos_debug_block_counters", "lithos_rightsize", "lithos_time_launch",
     "lithos_tenant_create", "lithos_tenant_destroy", "lithos_submit", "lithos_sync_mark", "lithos_sync",
@@ -264,6 +264,12 @@ def lithos_partition_stream(p) -> int:
     s = C.c_void_p()
     _check(lib().lithos_partition_stream(p, C.byref(s)))
     return s.value or 0
+
+
+def lithos_partitions_coupled(ctx, busy, probe) -> bool:
+    c = C.c_int()
+    _check(lib().lithos_partitions_coupled(ctx, busy, probe, C.byref(c)))
+    return bool(c.value)
 
 
 def lithos_probe_partition(ctx, p, n_wg):

@@ -284,7 +284,7 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 // ---- skinny: M <= 32 rows, B stored [N,K] -----------------------------------
 // out[m][n] = sum_k x[m][k] W[n][k] on MFMA 16x16x32 with the WEIGHTS as the
 // row operand: D[n][m] += W[n][k..k+31] x[m][k..k+31].  A workgroup owns 16*NB
-// output columns; its four wavefronts split K in quarters and their partial
+// output columns; its eight wavefronts split K in equal slices and their partial
 // tiles are added in wave order through LDS.  Every lane streams 16 bytes of
 // one weight row per step (64 contiguous bytes per row and step, rows walked
 // sequentially), so the weight matrix is read from HBM exactly once.
@@ -302,63 +302,53 @@ __device__ __forceinline__ bf16x8 pack_hi16(const float (&v)[8])
     return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
 }
 
-template <int MB, int NB, bool A32>
-__global__ __launch_bounds__(256)
-void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
-{
-    constexpr int U = 4;                        // k-steps whose loads are in flight together
-    __shared__ __attribute__((aligned(16))) float red[4][MB][NB][64][4];
+// One register buffer of the skinny kernel: U k-steps of weights and activations.
+template <int MB, int NB, bool A32, int U>
+struct SkinnyBuf {
+    uint4 wv[U][NB];
+    uint4 xv[U][MB][A32 ? 2 : 1];
 
-    const uint32_t L = atom_logical_block(atom);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r16 = lane & 15, kg = lane >> 4;
-    const int n0 = (int)L * 16 * NB;
-    // this wavefront's K range: quarters rounded to whole 32-wide steps
-    const int kq = ((g.K + 127) / 128) * 32;
-    const int kbeg = wave * kq, kend = min(g.K, kbeg + kq);
-
-    f32x4 acc[MB][NB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const uint16_t* wrow[NB];
-#pragma unroll
-    for (int j = 0; j < NB; ++j) wrow[j] = g.B + (int64_t)min(n0 + j * 16 + r16, g.N - 1) * g.ldb;
-    bool mlive[MB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i) mlive[i] = (i * 16 + r16) < g.M;
-
-    for (int k0 = kbeg; k0 < kend; k0 += 32 * U) {
-        uint4 wv[U][NB];
-        uint4 xv[U][MB][A32 ? 2 : 1];
+    // step = index of the first of U consecutive 32-wide k-steps; the slice is walked
+    // cyclically from a per-workgroup rotation so that the workgroups, whose weight rows
+    // are a power-of-two stride apart, do not all address the same memory channels.
+    __device__ __forceinline__ void load(const GemmArgs& g, const uint16_t* const (&wrow)[NB], const bool (&mlive)[MB],
+                                         int step, int nsteps, int rot, int kbeg, int kend, int r16, int kg)
+    {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int k = k0 + u * 32 + kg * 8;
-            const bool klive = k < kend;
+            // Loads are unconditional (addresses clamped into the matrix) and dead lanes are
+            // zeroed afterwards: straight-line loads let the hardware keep both register
+            // buffers' requests in flight, which branches around loads would prevent.
+            const int st = step + u;
+            const int k = kbeg + ((st + rot) % nsteps) * 32 + kg * 8;
+            const bool klive = st < nsteps && k < kend;
+            const int kc = min(k, g.K - 8);
+            const uint4 zero = make_uint4(0, 0, 0, 0);
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (klive) v = *reinterpret_cast<const uint4*>(wrow[j] + k);
-                wv[u][j] = v;
+                const uint4 v = *reinterpret_cast<const uint4*>(wrow[j] + kc);
+                wv[u][j] = klive ? v : zero;
             }
 #pragma unroll
             for (int i = 0; i < MB; ++i) {
-                uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
-                if (klive && mlive[i]) {
-                    if constexpr (A32) {
-                        const float* xp = reinterpret_cast<const float*>(g.A) + (int64_t)(i * 16 + r16) * g.lda + k;
-                        v0 = *reinterpret_cast<const uint4*>(xp);
-                        v1 = *reinterpret_cast<const uint4*>(xp + 4);
-                    } else {
-                        v0 = *reinterpret_cast<const uint4*>(g.A + (int64_t)(i * 16 + r16) * g.lda + k);
-                    }
+                const int64_t row = min(i * 16 + r16, g.M - 1);
+                const bool live = klive && mlive[i];
+                if constexpr (A32) {
+                    const float* xp = reinterpret_cast<const float*>(g.A) + row * g.lda + kc;
+                    const uint4 v0 = *reinterpret_cast<const uint4*>(xp);
+                    const uint4 v1 = *reinterpret_cast<const uint4*>(xp + 4);
+                    xv[u][i][0] = live ? v0 : zero;
+                    xv[u][i][1] = live ? v1 : zero;
+                } else {
+                    const uint4 v0 = *reinterpret_cast<const uint4*>(g.A + row * g.lda + kc);
+                    xv[u][i][0] = live ? v0 : zero;
                 }
-                xv[u][i][0] = v0;
-                if constexpr (A32) xv[u][i][1] = v1;
             }
         }
+    }
+
+    __device__ __forceinline__ void compute(f32x4 (&acc)[MB][NB]) const
+    {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -391,6 +381,49 @@ void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
             }
         }
     }
+};
+
+constexpr int SKINNY_WAVES = 8;     // wavefronts per workgroup, each owning one slice of K
+
+template <int MB, int NB, bool A32>
+__global__ __launch_bounds__(SKINNY_WAVES * 64)
+void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
+{
+    constexpr int U = 2, KW = SKINNY_WAVES;     // two register buffers of U k-steps each
+    __shared__ __attribute__((aligned(16))) float red[KW][MB][NB][64][4];
+
+    const uint32_t L = atom_logical_block(atom);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, kg = lane >> 4;
+    const int n0 = (int)L * 16 * NB;
+    // this wavefront's K range: equal slices rounded to whole 32-wide steps
+    const int kq = ((g.K + 32 * KW - 1) / (32 * KW)) * 32;
+    const int kbeg = wave * kq, kend = min(g.K, kbeg + kq);
+
+    f32x4 acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint16_t* wrow[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) wrow[j] = g.B + (int64_t)min(n0 + j * 16 + r16, g.N - 1) * g.ldb;
+    bool mlive[MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) mlive[i] = (i * 16 + r16) < g.M;
+
+    // software pipeline: the other buffer's loads are in flight while one is multiplied
+    const int nsteps = max(1, (kend - kbeg + 31) / 32);
+    const int rot = (int)((L * 7u + (uint32_t)wave * 3u) % (uint32_t)nsteps);
+    SkinnyBuf<MB, NB, A32, U> b0, b1;
+    b0.load(g, wrow, mlive, 0, nsteps, rot, kbeg, kend, r16, kg);
+    for (int st = 0; st < nsteps; st += 2 * U) {
+        b1.load(g, wrow, mlive, st + U, nsteps, rot, kbeg, kend, r16, kg);
+        b0.compute(acc);
+        b0.load(g, wrow, mlive, st + 2 * U, nsteps, rot, kbeg, kend, r16, kg);
+        b1.compute(acc);
+    }
 
 #pragma unroll
     for (int i = 0; i < MB; ++i)
@@ -399,7 +432,7 @@ void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
             *reinterpret_cast<f32x4*>(&red[wave][i][j][lane][0]) = acc[i][j];
     __syncthreads();
     if (wave == 0) {
-        // accumulator element e of a lane is D[n = 4*kg + e][m = r16]
+        // accumulator element e of a lane is D[n = 4*kg + e][m = r16]; slices are added in wave order
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -407,9 +440,8 @@ void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float v = red[0][i][j][lane][e];
-                    v += red[1][i][j][lane][e];
-                    v += red[2][i][j][lane][e];
-                    v += red[3][i][j][lane][e];
+#pragma unroll
+                    for (int w = 1; w < KW; ++w) v += red[w][i][j][lane][e];
                     epilogue_store(g, i * 16 + r16, n0 + j * 16 + 4 * kg + e, v);
                 }
     }
@@ -443,7 +475,7 @@ static gemm_fn tile_fn(int tile, bool ta, bool tb, bool split)
 #undef PICKS
 }
 
-static int tile_threads(int variant) { return variant == 30 ? 512 : 256; }
+static int tile_threads(int variant) { return variant == 30 ? 512 : variant < 10 ? SKINNY_WAVES * 64 : 256; }
 
 static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split)
 {

@@ -163,6 +163,22 @@ void default_config(lithos_config_t* c)
     c->ema_alpha = 0.25;
 }
 
+void retire_stream(lithos_ctx* ctx, hipStream_t s)
+{
+    if (!s) return;
+    std::lock_guard<std::mutex> lk(ctx->park_mu);
+    if (ctx->live_tenants.load() > 0) ctx->parked.push_back(s);
+    else (void)hipStreamDestroy(s);
+}
+
+void drain_parked(lithos_ctx* ctx)
+{
+    std::lock_guard<std::mutex> lk(ctx->park_mu);
+    // newest first: each removal then leaves the positions of the older queues alone
+    for (auto it = ctx->parked.rbegin(); it != ctx->parked.rend(); ++it) { (void)hipStreamSynchronize(*it); (void)hipStreamDestroy(*it); }
+    ctx->parked.clear();
+}
+
 } // namespace lithos
 
 using namespace lithos;
@@ -221,6 +237,7 @@ int lithos_shutdown(lithos_ctx_t* ctx)
     if (ctx->live_tenants.load() != 0) return fail(LITHOS_ESTATE, "lithos_shutdown: %d tenants still exist", ctx->live_tenants.load());
     (void)hipSetDevice(ctx->device);
     sched_shutdown(ctx);
+    drain_parked(ctx);
     (void)hipStreamSynchronize(ctx->plain);
     (void)hipStreamDestroy(ctx->plain);
     (void)hipEventDestroy(ctx->ev_in);
@@ -316,7 +333,7 @@ int lithos_destroy_partition(lithos_partition_t* p)
     if (!p) return fail(LITHOS_EINVAL, "lithos_destroy_partition: null partition");
     (void)hipSetDevice(p->ctx->device);
     (void)hipStreamSynchronize(p->stream);
-    (void)hipStreamDestroy(p->stream);
+    retire_stream(p->ctx, p->stream);
     delete p;
     return LITHOS_OK;
 }

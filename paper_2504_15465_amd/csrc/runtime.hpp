@@ -2,6 +2,8 @@
 #pragma once
 #include "common.hpp"
 #include <atomic>
+#include <mutex>
+#include <vector>
 
 namespace lithos { struct Scheduler; }
 
@@ -18,6 +20,8 @@ struct lithos_ctx {
     uint32_t n_counters = 0;
     std::atomic<int> live_tenants{0};
     lithos::Scheduler* sched = nullptr;   // created with the first tenant
+    std::mutex park_mu;
+    std::vector<hipStream_t> parked;      // retired queues kept alive while tenants exist
 };
 
 struct lithos_partition {
@@ -33,4 +37,9 @@ void default_config(lithos_config_t* c);
 AtomArgs make_atom(const lithos_ctx* ctx, const OpPlan& plan, uint32_t lo, uint32_t hi, int n_dies);
 int check_counters(const lithos_ctx* ctx, const OpPlan& plan);
 void sched_shutdown(lithos_ctx* ctx);
+// Destroying a queue moves every queue created after it to another command-processor
+// pipe, which can put two tenants' queues on one pipe.  While tenants exist a queue that
+// is no longer needed is therefore parked; parked queues go when the last tenant does.
+void retire_stream(lithos_ctx* ctx, hipStream_t s);
+void drain_parked(lithos_ctx* ctx);
 }

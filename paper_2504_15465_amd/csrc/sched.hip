@@ -21,6 +21,7 @@
 #include <mutex>
 #include <thread>
 #include <vector>
+#include <cstring>
 
 namespace lithos {
 
@@ -67,6 +68,70 @@ struct lithos_tenant {
 };
 
 namespace lithos {
+
+// ---- queue coupling ---------------------------------------------------------------
+// Hardware queues that the driver placed on the same command-processor pipe are
+// not independent: while one of them holds a grid that is only partly dispatched
+// (more workgroups than its CUs have room for), packets of the other queues on
+// that pipe wait.  A high-priority queue that shares a pipe with a best-effort
+// queue would therefore wait for whole best-effort atoms.  Which pipe a queue
+// gets is decided at creation and cannot be asked for, so it is measured: a
+// four-wave spin grid is started on queue `busy`, then a one-block kernel on
+// queue `probe`; if the latter takes as long as the grid, the two are coupled.
+static int queues_coupled(lithos_ctx* ctx, hipStream_t busy, int busy_cus, hipStream_t probe, bool* coupled)
+{
+    lithos_op_t big{}, tiny{};
+    big.kind = tiny.kind = LITHOS_OP_SPIN;
+    big.dim[0] = 8 * (int64_t)busy_cus;     // two blocks fit on a CU: four waves of blocks
+    big.dim[1] = 10000;                      // 100 us each
+    tiny.dim[0] = 1;
+    tiny.dim[1] = 1;
+    OpPlan pb, pt;
+    int rc = op_plan(big, &pb);
+    if (rc == LITHOS_OK) rc = op_plan(tiny, &pt);
+    if (rc != LITHOS_OK) return rc;
+    AtomArgs ab{0, pb.total, pb.grid.x, pb.grid.y, 1, nullptr}, at{0, 1, 1, 1, 1, nullptr};
+    LITHOS_HIP(hipStreamSynchronize(busy));
+    LITHOS_HIP(hipStreamSynchronize(probe));
+    rc = op_launch(big, pb, ab, busy);
+    if (rc != LITHOS_OK) return rc;
+    const double t0 = now_us();
+    rc = op_launch(tiny, pt, at, probe);
+    if (rc != LITHOS_OK) return rc;
+    LITHOS_HIP(hipStreamSynchronize(probe));
+    const double dt = now_us() - t0;
+    LITHOS_HIP(hipStreamSynchronize(busy));
+    *coupled = dt > 200.0;                   // uncoupled: tens of microseconds; coupled: ~300
+    return LITHOS_OK;
+}
+
+struct OtherQueue { hipStream_t stream; int cus; };
+
+// A CU-masked queue that is coupled with none of `others`.  The pipe of a queue
+// follows from its position among the process's live queues (measured: position
+// modulo the pipe count; destroying a queue moves all later ones up).  Queues are
+// therefore only ever appended here: a rejected candidate is parked, not destroyed,
+// so that the next candidate lands one position, and one pipe, further on.
+static int make_decoupled_stream(lithos_ctx* ctx, const uint32_t* mask, const std::vector<OtherQueue>& others, hipStream_t* out)
+{
+    const uint32_t words = (ctx->n_cu + 31) / 32;
+    for (int attempt = 0; attempt < 8; ++attempt) {
+        hipStream_t s = nullptr;
+        hipError_t e = hipExtStreamCreateWithCUMask(&s, words, mask);
+        if (e != hipSuccess) return fail(LITHOS_EHIP, "hipExtStreamCreateWithCUMask: %s", hipGetErrorString(e));
+        bool bad = false;
+        int rc = LITHOS_OK;
+        for (const OtherQueue& o : others) {
+            bool c = false;
+            rc = queues_coupled(ctx, o.stream, o.cus, s, &c);
+            if (rc != LITHOS_OK || c) { bad = true; break; }
+        }
+        if (!bad) { *out = s; return LITHOS_OK; }
+        { std::lock_guard<std::mutex> lk(ctx->park_mu); ctx->parked.push_back(s); }
+        if (rc != LITHOS_OK) return rc;
+    }
+    return fail(LITHOS_EHIP, "no CU-masked queue independent of the other tenants' queues after 8 attempts");
+}
 
 struct Scheduler {
     lithos_ctx* ctx;
@@ -271,6 +336,69 @@ int lithos_tenant_create(lithos_ctx_t* ctx, int cls, const lithos_partition_t* q
         if (t->group < 0) { (void)hipEventDestroy(t->switch_ev); delete t; return fail(LITHOS_ELIMIT, "lithos_tenant_create: at most 32 tenants per context"); }
         t->core_idx = s->core.add_tenant(cls, 1u << t->group);
         s->tenants.resize(t->core_idx + 1, nullptr);
+        // Queues of different tenants must not share a command-processor pipe: give this
+        // tenant a quota queue, and each pair of tenants their quota-plus-stolen queues,
+        // that are independent of every queue of the other tenants.
+        std::vector<OtherQueue> others;
+        for (lithos_tenant* o : s->tenants)
+            if (o) {
+                others.push_back({o->quota->stream, o->quota->n_cus});
+                for (auto& kv : o->streams) others.push_back({kv.second, s->core.cus_of(kv.first)});
+            }
+        if (!others.empty()) {
+            lithos_partition* q = const_cast<lithos_partition*>(quota);
+            bool coupled = false;
+            int rc = LITHOS_OK;
+            for (const OtherQueue& o : others) {
+                bool c = false;
+                rc = queues_coupled(ctx, o.stream, o.cus, q->stream, &c);
+                if (rc != LITHOS_OK) break;
+                coupled = coupled || c;
+            }
+            if (rc == LITHOS_OK && coupled) {
+                hipStream_t fresh = nullptr;
+                rc = make_decoupled_stream(ctx, q->mask, others, &fresh);
+                if (rc == LITHOS_OK) {
+                    std::lock_guard<std::mutex> pk(ctx->park_mu);
+                    ctx->parked.push_back(q->stream);           // parked, not destroyed: positions stay
+                    q->stream = fresh;
+                }
+            }
+            // quota + stolen queues, both directions, for every pair with an existing tenant
+            for (size_t i = 0; i < s->tenants.size() && rc == LITHOS_OK; ++i) {
+                lithos_tenant* o = s->tenants[i];
+                if (!o) continue;
+                const uint32_t gm = (1u << t->group) | (1u << o->group);
+                uint32_t mask[LITHOS_MASK_WORDS];
+                for (int w = 0; w < LITHOS_MASK_WORDS; ++w) mask[w] = q->mask[w] | o->quota->mask[w];
+                const int cus = q->n_cus + o->quota->n_cus;
+                // the new tenant's union queue: independent of all queues of all other tenants
+                hipStream_t mine = nullptr;
+                rc = make_decoupled_stream(ctx, mask, others, &mine);
+                if (rc != LITHOS_OK) break;
+                t->streams[gm] = mine;
+                // the existing tenant's union queue: independent of this tenant's queues (and third parties')
+                std::vector<OtherQueue> foes;
+                foes.push_back({q->stream, q->n_cus});
+                for (auto& kv : t->streams) foes.push_back({kv.second, cus});
+                for (lithos_tenant* x : s->tenants)
+                    if (x && x != o) {
+                        foes.push_back({x->quota->stream, x->quota->n_cus});
+                        for (auto& kv : x->streams) foes.push_back({kv.second, s->core.cus_of(kv.first)});
+                    }
+                hipStream_t theirs = nullptr;
+                rc = make_decoupled_stream(ctx, mask, foes, &theirs);
+                if (rc != LITHOS_OK) break;
+                o->streams[gm] = theirs;
+                others.push_back({theirs, cus});
+            }
+            if (rc != LITHOS_OK) {
+                for (auto& kv : t->streams) retire_stream(ctx, kv.second);
+                (void)hipEventDestroy(t->switch_ev);
+                delete t;
+                return rc;
+            }
+        }
         s->tenants[t->core_idx] = t;
     }
     ctx->live_tenants.fetch_add(1);
@@ -383,11 +511,11 @@ int lithos_tenant_destroy(lithos_tenant_t* t)
     } else {
         Scheduler* s = t->ctx->sched;
         std::lock_guard<std::mutex> lk(s->mu);
-        for (auto& kv : t->streams) { (void)hipStreamSynchronize(kv.second); (void)hipStreamDestroy(kv.second); }
+        for (auto& kv : t->streams) { (void)hipStreamSynchronize(kv.second); retire_stream(t->ctx, kv.second); }
         (void)hipEventDestroy(t->switch_ev);
         s->tenants[t->core_idx] = nullptr;   // its core slot stays (idle for ever): others may steal its CUs
     }
-    t->ctx->live_tenants.fetch_sub(1);
+    if (t->ctx->live_tenants.fetch_sub(1) == 1) drain_parked(t->ctx);
     delete t;
     return LITHOS_OK;
 }
@@ -501,3 +629,14 @@ int lithos_drive_closed_loop_stop(lithos_driver_t* d, uint64_t* iterations_out, 
 }
 
 } // extern "C"
+
+extern "C" int lithos_partitions_coupled(lithos_ctx_t* ctx, const lithos_partition_t* busy, const lithos_partition_t* probe, int* coupled_out)
+{
+    if (!ctx || !busy || !probe || !coupled_out || busy == probe) return fail(LITHOS_EINVAL, "lithos_partitions_coupled: bad argument");
+    (void)hipSetDevice(ctx->device);
+    bool c = false;
+    int rc = queues_coupled(ctx, busy->stream, busy->n_cus, probe->stream, &c);
+    if (rc != LITHOS_OK) return rc;
+    *coupled_out = c ? 1 : 0;
+    return LITHOS_OK;
+}

@@ -120,3 +120,28 @@ def test_overlapping_quotas_and_shutdown_with_tenants_are_refused():
         B.lithos_destroy_partition(p1)
         B.lithos_destroy_partition(p2)
         B.lithos_shutdown(c)
+
+
+def test_tenant_queues_do_not_share_a_command_processor_pipe():
+    """Queues created a multiple of the pipe count apart delay each other while a grid
+    is partly dispatched; tenant creation must hand out independent queues."""
+    c = B.lithos_init(0, None)
+    parts = [B.lithos_create_partition(c, B.lithos_make_mask(c, 24, B.MASK_STRIPED, 24 * i)) for i in range(9)]
+    try:
+        coupled = [B.lithos_partitions_coupled(c, parts[0], parts[j]) for j in range(1, 9)]
+        assert any(coupled), "expected at least one of 8 later queues to share a pipe with the first"
+        assert not all(coupled)
+        # tenants on partitions 0 and the first coupled one: creation must decouple them
+        j = 1 + coupled.index(True)
+        t0 = B.lithos_tenant_create(c, B.CLASS_HP, parts[0])
+        t1 = B.lithos_tenant_create(c, B.CLASS_BE, parts[j])
+        try:
+            assert not B.lithos_partitions_coupled(c, parts[0], parts[j])
+            assert not B.lithos_partitions_coupled(c, parts[j], parts[0])
+        finally:
+            B.lithos_tenant_destroy(t0)
+            B.lithos_tenant_destroy(t1)
+    finally:
+        for p in parts:
+            B.lithos_destroy_partition(p)
+        B.lithos_shutdown(c)
