@@ -40,7 +40,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per whole 8192^3 launch of the 256x256-tile GEMM, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # scaled by the 1 GiB copy calibration (profiles/): filled in by measurement, None until measured.
-TRAFFIC_BYTES = {256: None, 128: 3.36e9}
+TRAFFIC_BYTES = {256: 1.75e9, 128: 3.36e9}
 
 
 def nearest_rank(x, q):
@@ -298,11 +298,17 @@ def main():
     op, flop, desc = wl["be"]["dominant"]
     grid, wg_per_cu = B.lithos_op_grid(ctx, op)
     total_blocks = grid[0] * grid[1]
-    whole_mean, whole_med = B.lithos_time_launch(ctx, op, 0, p_all, 3, 20)
     atoms_per_kernel = max(1.0, (s1.atoms - s0.atoms) / max(1, (s1.kernels - s0.kernels)))
     quantum = 256 * wg_per_cu
     atom_blocks = min(total_blocks, -(-int(math.ceil(total_blocks / atoms_per_kernel)) // quantum) * quantum)
-    at_mean, at_med = B.lithos_time_launch(ctx, op, atom_blocks, p_all, 3, 20)
+    # whole and atomized launches alternate in short rounds so that clock and thermal
+    # drift hits both alike; the figures are medians (means for the roofline) over the rounds
+    B.lithos_time_launch(ctx, op, 0, p_all, 3, 3)
+    rounds = [(B.lithos_time_launch(ctx, op, 0, p_all, 1, 5), B.lithos_time_launch(ctx, op, atom_blocks, p_all, 1, 5))
+              for _ in range(8)]
+    whole_mean = float(np.mean([w[0] for w, _ in rounds]))
+    whole_med = float(np.median([w[1] for w, _ in rounds]))
+    at_med = float(np.median([a[1] for _, a in rounds]))
     overhead_pct = (at_med - whole_med) / whole_med * 100.0
     achieved = flop / (whole_mean * 1e-6) * 1e-12
     drop_world(B, ctx, parts + [p_all], [t_hp, t_be])

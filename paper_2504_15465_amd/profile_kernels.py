@@ -15,13 +15,15 @@ import torch
 
 from . import binding as B
 from . import inputs
-from .models import MlpChain
+from .models import DecoderChain, EncoderChain, MlpChain
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "mlp", "skinny"])
-    ap.add_argument("--tile", type=int, default=128)
+    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "mlp", "skinny", "encoder", "decoder"])
+    ap.add_argument("--tile", type=int, default=256)
+    ap.add_argument("--batch", type=int, default=4)
+    ap.add_argument("--layers", type=int, default=4)
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--cus", type=int, default=256)
     ap.add_argument("--copy-calibration", action="store_true")
@@ -55,6 +57,21 @@ def main():
         ops = chain.ops()
         if args.what == "skinny":
             ops = [o for o in ops if o.kind == B.OP_GEMM]
+        torch.cuda.synchronize()
+        for _ in range(args.reps):
+            for o in ops:
+                B.lithos_launch_atomized(ctx, o, (0, 0, 0), 0, part, None)
+        B.lithos_partition_sync(ctx, part)
+    elif args.what in ("encoder", "decoder"):
+        if args.what == "encoder":      # 12 layers, hidden 768, 12 heads, FFN 3072, sequences of 128
+            chain = EncoderChain(inputs.encoder_params(12, 768, 3072, seed=10), args.batch, 128, 12)
+            chain.set_input(inputs.encoder_hidden(args.batch, 128, 768, seed=11))
+        else:                           # hidden 4096, 32 query / 8 key-value heads, FFN 14336, 2048 cached positions
+            nl, H, nq, nkv, F, pos = args.layers, 4096, 32, 8, 14336, 2048
+            ks, vs = inputs.decoder_kv_cache(nl, args.batch, pos, nkv, H // nq, seed=21)
+            chain = DecoderChain(inputs.decoder_params(nl, H, nq, nkv, F, seed=20), ks, vs, args.batch, nq, nkv, pos)
+            chain.set_input(inputs.decoder_hidden(args.batch, H, seed=22))
+        ops = chain.ops()
         torch.cuda.synchronize()
         for _ in range(args.reps):
             for o in ops:
