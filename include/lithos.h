@@ -50,8 +50,11 @@ enum {
     LITHOS_OP_RMSNORM   = 7,  /* x / sqrt(mean(x^2)+eps) * w */
     LITHOS_OP_ROPE_KV   = 8,  /* rotary embedding of q and k (rotate-half) + append k,v to the cache */
     LITHOS_OP_SILU_MUL  = 9,  /* silu(gate) * up on a packed [rows, 2F] tensor */
-    LITHOS_OP_SPIN      = 10  /* test kernel: every block spins a fixed number of clock ticks */
+    LITHOS_OP_SPIN      = 10, /* test kernel: every block spins a fixed number of clock ticks */
+    LITHOS_OP_ATTN_MERGE = 11 /* second step of a split ATTN_DEC: merges the key ranges' partial softmaxes */
 };
+
+#define LITHOS_ATTN_MAX_SPLITS 64
 
 /* flags (meaning depends on the kind, see the table below) */
 #define LITHOS_F_TRANS_A   (1u << 0)   /* A is stored [K,M] */
@@ -79,8 +82,13 @@ enum {
  * LAYERNORM   rows,H                             x,gamma(f32),beta(f32) / y,[y_bf16]   fparam0=eps
  * SOFTMAX     rows,n                             s / p                                fparam0=scale
  * ATTN_ENC    batch,heads,seq,d                  qkv[batch*seq,3*heads*d] / o[batch*seq,heads*d]  fparam0=scale
- * ATTN_DEC    batch,n_q,n_kv,d,keys,cap          q,kcache,vcache / o                  ld0=q row stride; fparam0=scale
- *             caches are [batch,cap,n_kv,d] bf16; the first `keys` positions are read
+ * ATTN_DEC    batch,n_q,n_kv,d,keys,cap,splits   q,kcache,vcache,[workspace] / o      ld0=q row stride; fparam0=scale
+ *             caches are [batch,cap,n_kv,d] bf16; the first `keys` positions are read.
+ *             splits <= 1: one workgroup per (sequence, key/value head) writes o.
+ *             splits > 1: the keys are cut into `splits` ranges, one workgroup each, which write
+ *             partial softmaxes to the fp32 workspace in[3] (batch*n_q*splits*(d+2) floats) and
+ *             leave o untouched; ATTN_MERGE on the same queue then produces o.
+ * ATTN_MERGE  batch,n_q,n_kv,d,splits            workspace / o                        OUT_F32 as for ATTN_DEC
  * RMSNORM     rows,H                             x,w(f32) / y                         fparam0=eps
  * ROPE_KV     rows,n_q,n_kv,d,pos,cap            qkv[rows,(n_q+2n_kv)d] (in place) / kcache,vcache   fparam0=theta
  *             qkv is bf16, or fp32 with IN_F32; the caches are always bf16 (rounded on append)

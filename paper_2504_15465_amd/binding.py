@@ -20,7 +20,8 @@ OK, EINVAL, EHIP, EMASK, ESTATE, ELIMIT = 0, -1, -2, -3, -4, -5
 MASK_WORDS = 8
 MAX_SWEEP = 64
 
-OP_GEMM, OP_BIAS_ACT, OP_LAYERNORM, OP_SOFTMAX, OP_ATTN_ENC, OP_ATTN_DEC, OP_RMSNORM, OP_ROPE_KV, OP_SILU_MUL, OP_SPIN = range(1, 11)
+OP_GEMM, OP_BIAS_ACT, OP_LAYERNORM, OP_SOFTMAX, OP_ATTN_ENC, OP_ATTN_DEC, OP_RMSNORM, OP_ROPE_KV, OP_SILU_MUL, OP_SPIN, OP_ATTN_MERGE = range(1, 12)
+ATTN_MAX_SPLITS = 64
 F_TRANS_A, F_TRANS_B, F_BIAS, F_GELU, F_RESIDUAL, F_OUT_F32, F_IN_F32, F_SPLIT_A, F_OUT_SPLIT = (1 << i for i in range(9))
 TILE_AUTO, TILE_SKINNY, TILE_64, TILE_128, TILE_256 = 0, 1, 64, 128, 256
 MASK_STRIPED, MASK_WHOLE_XCD = 0, 1
@@ -209,10 +210,22 @@ def attn_enc_op(qkv, o, batch, heads, seq, d, scale, op_id=0, split=False) -> Op
                    inputs=(qkv,), outputs=(o,), op_id=op_id)
 
 
-def attn_dec_op(q, kcache, vcache, o, batch, n_q, n_kv, d, keys, cap, scale, ldq=None, op_id=0) -> Op:
+def attn_dec_op(q, kcache, vcache, o, batch, n_q, n_kv, d, keys, cap, scale, ldq=None, op_id=0,
+                splits=1, workspace=None) -> Op:
+    """splits > 1 needs an fp32 workspace of attn_workspace_floats(...) elements and an attn_merge_op after it."""
     flags = (F_IN_F32 if q.dtype == torch.float32 else 0) | (F_OUT_F32 if o.dtype == torch.float32 else 0)
-    return make_op(OP_ATTN_DEC, (batch, n_q, n_kv, d, keys, cap), flags, ld=(ldq if ldq is not None else n_q * d,),
-                   fparam=(scale,), inputs=(q, kcache, vcache), outputs=(o,), op_id=op_id)
+    ins = (q, kcache, vcache) if workspace is None else (q, kcache, vcache, workspace)
+    return make_op(OP_ATTN_DEC, (batch, n_q, n_kv, d, keys, cap, splits), flags, ld=(ldq if ldq is not None else n_q * d,),
+                   fparam=(scale,), inputs=ins, outputs=(o,), op_id=op_id)
+
+
+def attn_workspace_floats(batch, n_q, d, splits) -> int:
+    return batch * n_q * splits * (d + 2)
+
+
+def attn_merge_op(workspace, o, batch, n_q, n_kv, d, splits, op_id=0) -> Op:
+    flags = F_OUT_F32 if o.dtype == torch.float32 else 0
+    return make_op(OP_ATTN_MERGE, (batch, n_q, n_kv, d, splits), flags, inputs=(workspace,), outputs=(o,), op_id=op_id)
 
 
 def spin_op(blocks, ticks, op_id=0) -> Op:

@@ -33,6 +33,8 @@ struct AttnArgs {
     int64_t ldq;
     float scale;
     uint32_t flags;
+    int splits;             // dec: key ranges per (sequence, key/value head)
+    float* ws;              // dec with splits > 1: partial softmaxes
 };
 
 __device__ __forceinline__ uint16_t attn_f32_to_bf16(float f)
@@ -161,109 +163,196 @@ __global__ __launch_bounds__(256) void attn_enc_kernel(AttnArgs a, AtomArgs atom
 }
 
 // ---- decode, grouped-query -------------------------------------------------------
-// G = query heads per key/value head (1, 2 or 4), D = 128.
-// Phase per 64-key batch of a wavefront: lane = key for the scores (q is read
-// from LDS with broadcast reads), lane = d-pair for the value sum (probabilities
-// are broadcast with readlane).
+// G = query heads per key/value head (1, 2 or 4), D = 128.  The keys of one
+// (sequence, key/value head) are cut into `splits` contiguous ranges of 32-key
+// units, one workgroup each, so that a partition's CUs all stream the cache.
+//
+// Lane layout: the 16 lanes of a DPP row share one key; lane c of the row owns
+// head dimensions 8c..8c+7, so a row reads one 256-byte cache row with 16-byte
+// loads and four rows of a wavefront read four neighbouring tokens.  A score is
+// the lane's partial dot product summed over its row (4 DPP steps, after which
+// all 16 lanes hold the same bits), the value sum needs no exchange at all, and
+// each of the 16 rows of a workgroup keeps its own running softmax.  The 16
+// partial softmaxes are merged in a fixed order, then the splits (attn_merge).
+__device__ __forceinline__ float dpp_row_sum(float x)
+{
+#define LITHOS_DPP_ADD(CTRL) x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false))
+    LITHOS_DPP_ADD(0xB1);    // quad_perm [1,0,3,2]
+    LITHOS_DPP_ADD(0x4E);    // quad_perm [2,3,0,1]
+    LITHOS_DPP_ADD(0x141);   // row_half_mirror: the other quad of the same 8 lanes
+    LITHOS_DPP_ADD(0x140);   // row_mirror: the other 8 lanes of the row
+#undef LITHOS_DPP_ADD
+    return x;
+}
+
+__device__ __forceinline__ void unpack_bf16x8(const uint4& u, float* f)
+{
+    f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
+    f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
+    f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xffff0000u);
+    f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
+}
+
+// Workspace of a split launch (floats): numerators [batch*n_kv][splits][G][D],
+// then (max, denominator) pairs [batch*n_kv][splits][G][2].
 template <int G, bool Q32, bool O32>
 __global__ __launch_bounds__(256) void attn_dec_kernel(AttnArgs a, AtomArgs atom)
 {
-    constexpr int D = 128;
-    __shared__ __attribute__((aligned(16))) float qs[G * D];
-    __shared__ float part_m[4][G], part_l[4][G];
-    __shared__ __attribute__((aligned(16))) float part_o[4][G][D];
+    constexpr int D = 128, R = 8;                 // R keys per lane and step: 32 keys per wavefront step
+    __shared__ float part_m[16][G], part_l[16][G];
+    __shared__ __attribute__((aligned(16))) float part_o[16][G][D];
 
     const uint32_t L = atom_logical_block(atom);
-    const int b = L / a.n_kv, g = L % a.n_kv;
+    const int S = a.splits;
+    const int sp = L % S, bg = L / S;
+    const int b = bg / a.n_kv, g = bg % a.n_kv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, rg = lane >> 4;
 
-    for (int i = tid; i < G * D; i += 256) {
-        int64_t idx = (int64_t)b * a.ldq + (g * G) * D + i;
-        float v;
-        if constexpr (Q32) v = reinterpret_cast<const float*>(a.q)[idx];
-        else v = attn_bf16_to_f32(reinterpret_cast<const uint16_t*>(a.q)[idx]);
-        qs[i] = v * a.scale;
+    float qf[G][8];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const int64_t idx = (int64_t)b * a.ldq + (g * G + h) * D + 8 * c;
+        if constexpr (Q32) {
+            const float4 q0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.q) + idx);
+            const float4 q1 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.q) + idx + 4);
+            qf[h][0] = q0.x; qf[h][1] = q0.y; qf[h][2] = q0.z; qf[h][3] = q0.w;
+            qf[h][4] = q1.x; qf[h][5] = q1.y; qf[h][6] = q1.z; qf[h][7] = q1.w;
+        } else {
+            unpack_bf16x8(*reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(a.q) + idx), qf[h]);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[h][e] *= a.scale;
     }
-    __syncthreads();
 
     const int64_t tok_stride = (int64_t)a.n_kv * D;
-    const uint16_t* kbase = a.k + ((int64_t)b * a.cap * a.n_kv + g) * D;
-    const uint16_t* vbase = a.v + ((int64_t)b * a.cap * a.n_kv + g) * D;
+    const uint16_t* kbase = a.k + ((int64_t)b * a.cap * a.n_kv + g) * D + 8 * c;
+    const uint16_t* vbase = a.v + ((int64_t)b * a.cap * a.n_kv + g) * D + 8 * c;
     const int T = a.seq;
+    const int U = (T + 31) / 32;                                   // 32-key units
+    const int u0 = (int)((int64_t)sp * U / S), u1 = (int)((int64_t)(sp + 1) * U / S);
 
-    float m[G], l[G], acc[G][2];
+    float m[G], l[G], acc[G][8];
 #pragma unroll
-    for (int h = 0; h < G; ++h) { m[h] = -INFINITY; l[h] = 0.0f; acc[h][0] = acc[h][1] = 0.0f; }
+    for (int h = 0; h < G; ++h) {
+        m[h] = -INFINITY; l[h] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
+    }
 
-    for (int t0 = wave * 64; t0 < T; t0 += 256) {
-        const int t = t0 + lane;
-        const bool live = t < T;
-        float sc[G];
+    for (int u = u0 + wave; u < u1; u += 4) {
+        uint4 kx[R], vx[R];
 #pragma unroll
-        for (int h = 0; h < G; ++h) sc[h] = 0.0f;
-        const uint16_t* krow = kbase + (int64_t)(live ? t : T - 1) * tok_stride;
+        for (int i = 0; i < R; ++i) {
+            const int t = 32 * u + 4 * i + rg;
+            const int64_t off = (int64_t)min(t, T - 1) * tok_stride;    // dead keys read the last live row
+            kx[i] = *reinterpret_cast<const uint4*>(kbase + off);
+            vx[i] = *reinterpret_cast<const uint4*>(vbase + off);
+        }
+        float sc[R][G];
 #pragma unroll
-        for (int c = 0; c < D / 8; ++c) {
-            uint4 kv = *reinterpret_cast<const uint4*>(krow + c * 8);
-            uint32_t u[4] = {kv.x, kv.y, kv.z, kv.w};
+        for (int i = 0; i < R; ++i) {
             float kf[8];
-#pragma unroll
-            for (int p = 0; p < 4; ++p) { kf[2 * p] = __uint_as_float(u[p] << 16); kf[2 * p + 1] = __uint_as_float(u[p] & 0xffff0000u); }
+            unpack_bf16x8(kx[i], kf);
+            const bool live = 32 * u + 4 * i + rg < T;
 #pragma unroll
             for (int h = 0; h < G; ++h) {
-                const float4 q0 = *reinterpret_cast<const float4*>(qs + h * D + c * 8);
-                const float4 q1 = *reinterpret_cast<const float4*>(qs + h * D + c * 8 + 4);
-                sc[h] += kf[0] * q0.x + kf[1] * q0.y + kf[2] * q0.z + kf[3] * q0.w
-                       + kf[4] * q1.x + kf[5] * q1.y + kf[6] * q1.z + kf[7] * q1.w;
+                float d = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d += kf[e] * qf[h][e];
+                d = dpp_row_sum(d);
+                sc[i][h] = live ? d : -INFINITY;
             }
         }
-        float p[G];
 #pragma unroll
         for (int h = 0; h < G; ++h) {
-            float s = live ? sc[h] : -INFINITY;
-            float bm = s;
+            float bm = sc[0][h];
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) bm = fmaxf(bm, __shfl_xor(bm, off, 64));
+            for (int i = 1; i < R; ++i) bm = fmaxf(bm, sc[i][h]);
             const float nm = fmaxf(m[h], bm);
-            const float corr = expf(m[h] - nm);           // 0 on the first batch (m = -inf)
-            p[h] = live ? expf(s - nm) : 0.0f;
-            float bs = p[h];
+            const float ref = nm == -INFINITY ? 0.0f : nm;        // a row that has seen no live key yet
+            const float corr = expf(m[h] - ref);                  // 0 while m = -inf
+            float ls = l[h] * corr;
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) bs += __shfl_xor(bs, off, 64);
-            l[h] = l[h] * corr + bs;
-            acc[h][0] *= corr; acc[h][1] *= corr;
+            for (int e = 0; e < 8; ++e) acc[h][e] *= corr;
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                const float p = expf(sc[i][h] - ref);             // 0 for a dead key
+                ls += p;
+                sc[i][h] = p;
+            }
+            l[h] = ls;
             m[h] = nm;
         }
-        // value sum: lane owns d = 2*lane, 2*lane+1
-        const int nkeys = min(64, T - t0);
-        for (int j = 0; j < nkeys; ++j) {
-            const uint32_t vv = *reinterpret_cast<const uint32_t*>(vbase + (int64_t)(t0 + j) * tok_stride + 2 * lane);
-            const float v0 = __uint_as_float(vv << 16), v1 = __uint_as_float(vv & 0xffff0000u);
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const float pj = __shfl(p[h], j, 64);
-                acc[h][0] += pj * v0;
-                acc[h][1] += pj * v1;
-            }
+        for (int i = 0; i < R; ++i) {
+            float vf[8];
+            unpack_bf16x8(vx[i], vf);
+#pragma unroll
+            for (int h = 0; h < G; ++h)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[h][e] += sc[i][h] * vf[e];
         }
     }
 
-    // merge the four wavefronts' partial softmaxes in wave order
-    if (lane == 0)
+    // merge the 16 rows' partial softmaxes (wavefront-major, then row) in that order
+    const int slot = wave * 4 + rg;
 #pragma unroll
-        for (int h = 0; h < G; ++h) { part_m[wave][h] = m[h]; part_l[wave][h] = l[h]; }
-#pragma unroll
-    for (int h = 0; h < G; ++h) { part_o[wave][h][2 * lane] = acc[h][0]; part_o[wave][h][2 * lane + 1] = acc[h][1]; }
+    for (int h = 0; h < G; ++h) {
+        if (c == 0) { part_m[slot][h] = m[h]; part_l[slot][h] = l[h]; }
+        *reinterpret_cast<float4*>(&part_o[slot][h][8 * c]) = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
+        *reinterpret_cast<float4*>(&part_o[slot][h][8 * c + 4]) = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
+    }
     __syncthreads();
     for (int i = tid; i < G * D; i += 256) {
         const int h = i / D, d = i % D;
         float gm = -INFINITY;
-        for (int w = 0; w < 4; ++w) gm = fmaxf(gm, part_m[w][h]);
+        for (int w = 0; w < 16; ++w) gm = fmaxf(gm, part_m[w][h]);
+        const float ref = gm == -INFINITY ? 0.0f : gm;            // a split without keys: all partials empty
         float num = 0.0f, den = 0.0f;
-        for (int w = 0; w < 4; ++w) {
-            const float f = expf(part_m[w][h] - gm);      // 0 for a wavefront that saw no key
+        for (int w = 0; w < 16; ++w) {
+            const float f = expf(part_m[w][h] - ref);             // 0 for a row that saw no key
             num += part_o[w][h][d] * f;
             den += part_l[w][h] * f;
+        }
+        if (S == 1) {
+            const float r = num / den;
+            const int64_t idx = (int64_t)b * ((int64_t)a.n_q * D) + (g * G + h) * D + d;
+            if constexpr (O32) reinterpret_cast<float*>(a.o)[idx] = r;
+            else reinterpret_cast<uint16_t*>(a.o)[idx] = attn_f32_to_bf16(r);
+        } else {
+            float* ws = a.ws;
+            const int64_t row = ((int64_t)bg * S + sp) * G + h;
+            ws[row * D + d] = num;
+            if (d == 0) {
+                float* ml = ws + (int64_t)a.batch * a.n_kv * S * G * D;
+                ml[row * 2] = gm;
+                ml[row * 2 + 1] = den;
+            }
+        }
+    }
+}
+
+// Merge of the splits' partial softmaxes, in split order.  One workgroup per
+// (sequence, key/value head).
+template <int G, bool O32>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, AtomArgs atom)
+{
+    constexpr int D = 128;
+    const uint32_t bg = atom_logical_block(atom);
+    const int b = bg / a.n_kv, g = bg % a.n_kv, S = a.splits;
+    const float* ws = a.ws;
+    const float* ml = ws + (int64_t)a.batch * a.n_kv * S * G * D;
+    for (int i = threadIdx.x; i < G * D; i += 256) {
+        const int h = i / D, d = i % D;
+        float gm = -INFINITY;
+        for (int s = 0; s < S; ++s) gm = fmaxf(gm, ml[(((int64_t)bg * S + s) * G + h) * 2]);
+        float num = 0.0f, den = 0.0f;
+        for (int s = 0; s < S; ++s) {
+            const int64_t row = ((int64_t)bg * S + s) * G + h;
+            const float f = expf(ml[row * 2] - gm);               // 0 for a split without keys
+            num += ws[row * D + d] * f;
+            den += ml[row * 2 + 1] * f;
         }
         const float r = num / den;
         const int64_t idx = (int64_t)b * ((int64_t)a.n_q * D) + (g * G + h) * D + d;
@@ -304,8 +393,23 @@ int attn_plan(const lithos_op_t& op, OpPlan* plan)
         plan->wg_per_cu = 2;
         return LITHOS_OK;
     }
-    // decode: dim = batch, n_q, n_kv, d, keys, cap
+    if (op.kind == LITHOS_OP_ATTN_MERGE) {
+        // dim = batch, n_q, n_kv, d, splits
+        const int64_t batch = op.dim[0], n_q = op.dim[1], n_kv = op.dim[2], d = op.dim[3], splits = op.dim[4];
+        if (batch <= 0 || n_q <= 0 || n_kv <= 0 || n_q % n_kv || batch * n_kv > 0x7fffffff) return fail(LITHOS_EINVAL, "attn_merge: need batch > 0 and n_kv dividing n_q");
+        const int64_t G = n_q / n_kv;
+        if (G != 1 && G != 2 && G != 4) return fail(LITHOS_EINVAL, "attn_merge: group size %lld is not built (1, 2, 4)", (long long)G);
+        if (d != 128) return fail(LITHOS_EINVAL, "attn_merge: head width %lld is not built (128 only)", (long long)d);
+        if (splits < 1 || splits > LITHOS_ATTN_MAX_SPLITS) return fail(LITHOS_EINVAL, "attn_merge: splits %lld outside 1..%d", (long long)splits, LITHOS_ATTN_MAX_SPLITS);
+        if (!op.in[0] || !op.out[0]) return fail(LITHOS_EINVAL, "attn_merge: null operand");
+        plan->grid = {(uint32_t)n_kv, (uint32_t)batch, 1};
+        plan->total = (uint32_t)(batch * n_kv);
+        plan->wg_per_cu = 4;
+        return LITHOS_OK;
+    }
+    // decode: dim = batch, n_q, n_kv, d, keys, cap, splits
     const int64_t batch = op.dim[0], n_q = op.dim[1], n_kv = op.dim[2], d = op.dim[3], keys = op.dim[4], cap = op.dim[5];
+    const int64_t splits = op.dim[6] > 0 ? op.dim[6] : 1;
     if (batch <= 0 || n_q <= 0 || n_kv <= 0 || n_q % n_kv) return fail(LITHOS_EINVAL, "attn_dec: need batch > 0 and n_kv dividing n_q");
     const int64_t G = n_q / n_kv;
     if (G != 1 && G != 2 && G != 4) return fail(LITHOS_EINVAL, "attn_dec: group size %lld is not built (1, 2, 4)", (long long)G);
@@ -314,9 +418,13 @@ int attn_plan(const lithos_op_t& op, OpPlan* plan)
     if (op.ld[0] < n_q * d) return fail(LITHOS_EINVAL, "attn_dec: q row stride smaller than n_q*d");
     if (!op.in[0] || !op.in[1] || !op.in[2] || !op.out[0]) return fail(LITHOS_EINVAL, "attn_dec: null operand");
     if (!aligned16(op.in[1]) || !aligned16(op.in[2])) return fail(LITHOS_EINVAL, "attn_dec: caches must be 16-byte aligned");
-    plan->grid = {(uint32_t)n_kv, (uint32_t)batch, 1};
-    plan->total = (uint32_t)(batch * n_kv);
-    plan->wg_per_cu = 4;
+    if (!aligned16(op.in[0]) || op.ld[0] % 8) return fail(LITHOS_EINVAL, "attn_dec: q must be 16-byte aligned with a row stride that is a multiple of 8");
+    if (splits > LITHOS_ATTN_MAX_SPLITS) return fail(LITHOS_EINVAL, "attn_dec: splits %lld above %d", (long long)splits, LITHOS_ATTN_MAX_SPLITS);
+    if (splits > 1 && (!op.in[3] || !aligned16(op.in[3]))) return fail(LITHOS_EINVAL, "attn_dec: a split launch needs a 16-byte aligned workspace in in[3]");
+    if (batch * n_kv * splits > 0x7fffffff) return fail(LITHOS_EINVAL, "attn_dec: too many workgroups");
+    plan->grid = {(uint32_t)(n_kv * splits), (uint32_t)batch, 1};
+    plan->total = (uint32_t)(batch * n_kv * splits);
+    plan->wg_per_cu = 2;
     return LITHOS_OK;
 }
 
@@ -334,8 +442,21 @@ int attn_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
         LITHOS_HIP(launch_kernel(fn, grid, block, s, a, atom));
         return LITHOS_OK;
     }
+    if (op.kind == LITHOS_OP_ATTN_MERGE) {
+        a.batch = (int)op.dim[0]; a.n_q = (int)op.dim[1]; a.n_kv = (int)op.dim[2]; a.d = (int)op.dim[3]; a.splits = (int)op.dim[4];
+        a.ws = (float*)const_cast<void*>(op.in[0]);
+        const int G = a.n_q / a.n_kv;
+        const bool o32 = op.flags & LITHOS_F_OUT_F32;
+        attn_fn fn = G == 1 ? (o32 ? (attn_fn)attn_merge_kernel<1, true> : (attn_fn)attn_merge_kernel<1, false>)
+                   : G == 2 ? (o32 ? (attn_fn)attn_merge_kernel<2, true> : (attn_fn)attn_merge_kernel<2, false>)
+                            : (o32 ? (attn_fn)attn_merge_kernel<4, true> : (attn_fn)attn_merge_kernel<4, false>);
+        LITHOS_HIP(launch_kernel(fn, grid, block, s, a, atom));
+        return LITHOS_OK;
+    }
     a.k = (const uint16_t*)op.in[1];
     a.v = (const uint16_t*)op.in[2];
+    a.splits = op.dim[6] > 0 ? (int)op.dim[6] : 1;
+    a.ws = (float*)const_cast<void*>(op.in[3]);
     a.batch = (int)op.dim[0]; a.n_q = (int)op.dim[1]; a.n_kv = (int)op.dim[2]; a.d = (int)op.dim[3];
     a.seq = (int)op.dim[4]; a.cap = (int)op.dim[5];
     a.ldq = op.ld[0];

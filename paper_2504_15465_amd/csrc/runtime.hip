@@ -55,6 +55,7 @@ int op_plan(const lithos_op_t& op, OpPlan* plan)
     switch (op.kind) {
     case LITHOS_OP_GEMM: return gemm_plan(op, plan);
     case LITHOS_OP_ATTN_ENC:
+    case LITHOS_OP_ATTN_MERGE:
     case LITHOS_OP_ATTN_DEC: return attn_plan(op, plan);
     case LITHOS_OP_BIAS_ACT:
     case LITHOS_OP_LAYERNORM:
@@ -73,6 +74,7 @@ int op_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, h
     switch (op.kind) {
     case LITHOS_OP_GEMM: return gemm_launch(op, plan, atom, s);
     case LITHOS_OP_ATTN_ENC:
+    case LITHOS_OP_ATTN_MERGE:
     case LITHOS_OP_ATTN_DEC: return attn_launch(op, plan, atom, s);
     default: return rowops_launch(op, plan, atom, s);
     }

@@ -156,8 +156,12 @@ class DecoderChain:
     key/value cache.  All GEMMs are the weight-streaming kind (weights [N,K],
     fp32 activations); the cache slot ``pos`` is rewritten on every step."""
 
-    def __init__(self, layers, kcache_bits, vcache_bits, batch: int, n_q: int, n_kv: int, pos: int, device="cuda"):
+    def __init__(self, layers, kcache_bits, vcache_bits, batch: int, n_q: int, n_kv: int, pos: int, device="cuda",
+                 splits: int = 0):
         self.batch, self.n_q, self.n_kv, self.pos = batch, n_q, n_kv, pos
+        # key ranges per (sequence, key/value head): enough workgroups for a few hundred CU slots
+        units = (pos + 1 + 31) // 32
+        self.splits = splits if splits > 0 else max(1, min(B.ATTN_MAX_SPLITS, units, -(-256 // (batch * n_kv))))
         H = layers[0]["w_qkv"].shape[0]
         self.H = H
         self.d = H // n_q
@@ -181,6 +185,7 @@ class DecoderChain:
         self.n = torch.zeros((batch, H), dtype=f32, device=device)
         self.qkv = torch.zeros((batch, nqkv), dtype=f32, device=device)
         self.att = torch.zeros((batch, n_q * self.d), dtype=f32, device=device)
+        self.ws = torch.zeros(B.attn_workspace_floats(batch, n_q, self.d, self.splits), dtype=f32, device=device)
         self.gu = torch.zeros((batch, 2 * self.F), dtype=f32, device=device)
         self.act = torch.zeros((batch, self.F), dtype=f32, device=device)
         self.out = self.x
@@ -189,13 +194,18 @@ class DecoderChain:
         Bn, H, F, d, n_q, n_kv = self.batch, self.H, self.F, self.d, self.n_q, self.n_kv
         nqkv = (n_q + 2 * n_kv) * d
         ops = [B.bias_act_op(self.x_in, self.x, Bn, H, None, gelu=False)]      # working copy of the input
+        S = self.splits
         for li, W in enumerate(self.w):
             ops += [
                 B.rmsnorm_op(self.x, W["rms1"], self.n, Bn, H),
                 B.gemm_op(self.n, W["w_qkv"], self.qkv, Bn, nqkv, H, tb=True),
                 B.rope_kv_op(self.qkv, self.kc[li], self.vc[li], Bn, n_q, n_kv, d, self.pos, self.cap),
                 B.attn_dec_op(self.qkv, self.kc[li], self.vc[li], self.att, Bn, n_q, n_kv, d, self.pos + 1, self.cap,
-                              1.0 / math.sqrt(d), ldq=nqkv),
+                              1.0 / math.sqrt(d), ldq=nqkv, splits=S, workspace=self.ws if S > 1 else None),
+            ]
+            if S > 1:
+                ops.append(B.attn_merge_op(self.ws, self.att, Bn, n_q, n_kv, d, S))
+            ops += [
                 B.gemm_op(self.att, W["w_o"], self.x, Bn, H, n_q * d, tb=True, residual=self.x),
                 B.rmsnorm_op(self.x, W["rms2"], self.n, Bn, H),
                 B.gemm_op(self.n, W["w_gu"], self.gu, Bn, 2 * F, H, tb=True),

@@ -65,9 +65,13 @@ def test_encoder_attention_special_cases():
     assert np.abs(g - v[None, :]).max() <= 2.0 ** -7 * np.abs(v).max() + 1e-3       # O = V when V is constant
 
 
-@pytest.mark.parametrize("batch,n_q,n_kv,keys", [(1, 32, 8, 2049), (3, 8, 8, 70), (2, 4, 2, 300), (16, 32, 8, 257)])
+@pytest.mark.parametrize("batch,n_q,n_kv,keys,splits", [
+    (1, 32, 8, 2049, 1), (1, 32, 8, 2049, 8), (4, 32, 8, 2049, 9), (3, 8, 8, 70, 1), (3, 8, 8, 70, 2), (2, 4, 2, 300, 5),
+    (16, 32, 8, 257, 3), (2, 8, 4, 1, 4), (2, 8, 4, 31, 1), (1, 4, 1, 33, 7), (1, 8, 2, 4096, 64)])
 @pytest.mark.parametrize("q32", [True, False])
-def test_decode_attention(batch, n_q, n_kv, keys, q32):
+def test_decode_attention(batch, n_q, n_kv, keys, splits, q32):
+    """One workgroup per key range; ranges without any key (more splits than 32-key units)
+    and a ragged last unit are part of the cases."""
     d, cap = 128, keys + 3
     qb = inputs.normal_bits((batch, n_q * d), 41)
     kb = inputs.normal_bits((batch, cap, n_kv, d), 42)
@@ -77,17 +81,37 @@ def test_decode_attention(batch, n_q, n_kv, keys, q32):
     q = dev_bits(qb)
     if q32:
         q = q.float()
-    o = nan_like((batch, n_q * d), torch.float32 if q32 else torch.bfloat16)
     k, v = dev_bits(kb), dev_bits(vb)
-    total = launch(B.attn_dec_op(q, k, v, o, batch, n_q, n_kv, d, keys, cap, 1 / math.sqrt(d)))
-    assert total == batch * n_kv
+    ws = nan_like((B.attn_workspace_floats(batch, n_q, d, splits),), torch.float32) if splits > 1 else None
+
+    def run(atom_blocks, merge_atom):
+        o = nan_like((batch, n_q * d), torch.float32 if q32 else torch.bfloat16)
+        if ws is not None:
+            ws.fill_(float("nan"))
+        total = launch(B.attn_dec_op(q, k, v, o, batch, n_q, n_kv, d, keys, cap, 1 / math.sqrt(d), splits=splits, workspace=ws),
+                       atom_blocks)
+        assert total == batch * n_kv * splits
+        if splits > 1:
+            assert launch(B.attn_merge_op(ws, o, batch, n_q, n_kv, d, splits), merge_atom) == batch * n_kv
+        return o
+
+    o = run(0, 0)
     if q32:
         assert np.abs(o.cpu().numpy().astype(np.float64) - ref).max() <= 2e-5
     else:
         bf16_close(o, ref, abs_tol=2e-5)
-    oa = nan_like(o.shape, o.dtype)
-    launch(B.attn_dec_op(q, k, v, oa, batch, n_q, n_kv, d, keys, cap, 1 / math.sqrt(d)), atom_blocks=3)
-    assert bits_equal(o, oa)
+    assert bits_equal(o, run(3, 1))
+
+
+def test_decode_attention_split_needs_workspace():
+    x = torch.zeros((4, 4 * 128), dtype=torch.float32, device="cuda")
+    kv = torch.zeros((4, 64, 4, 128), dtype=torch.bfloat16, device="cuda")
+    for op in (B.attn_dec_op(x, kv, kv, x, 4, 4, 4, 128, 64, 64, 1.0, splits=2),
+               B.attn_dec_op(x, kv, kv, x, 4, 4, 4, 128, 64, 64, 1.0, splits=65, workspace=x),
+               B.attn_merge_op(x, x, 4, 4, 4, 128, 0)):
+        with pytest.raises(B.LithosError) as e:
+            B.lithos_launch_atomized(ctx(), op)
+        assert e.value.code == B.EINVAL
 
 
 def test_attention_refuses_unbuilt_shapes():
