@@ -281,6 +281,144 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
     });
 }
 
+// ---- 256x256 tile, both operands k-contiguous, global -> LDS without registers ---
+// C = A B^T with A [M,K] and B [N,K] (TRANS_B), K a multiple of 64.  The k-tiles go
+// from global memory straight into LDS (global_load_lds_dwordx4: the 64 lanes of a
+// wavefront fill 1 KB of LDS in lane order, so each lane fetches the 16-byte chunk
+// that the swizzled layout wants at its position).  That frees the 32 staging
+// registers of the general kernel, which pay for a second set of operand fragments:
+// the LDS reads of step kk+1 are issued before the MFMAs of step kk.
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int WGM, int WGN>
+__global__ __launch_bounds__(WGM * WGN * 64)
+void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
+{
+    constexpr int BM = 256, BN = 256, BK = 64, WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
+    constexpr int NBLK = 32 / (WGM * WGN);          // 1 KB blocks of each operand that a wavefront fetches
+    // four separate arrays, each addressed statically: the compiler can then tell that the
+    // LDS reads of one stage do not depend on the loads in flight into the other
+    __shared__ __attribute__((aligned(1024))) uint16_t A0[BM * BK];
+    __shared__ __attribute__((aligned(1024))) uint16_t A1[BM * BK];
+    __shared__ __attribute__((aligned(1024))) uint16_t B0[BN * BK];
+    __shared__ __attribute__((aligned(1024))) uint16_t B1[BN * BK];
+
+    const uint32_t L = atom_logical_block(atom);
+    const Block3 blk = atom_delinearize(L, atom);
+    uint32_t tm, tn;
+    tile_of_block((blk.z * atom.gy + blk.y) * atom.gx + blk.x, g.tiles_m, g.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // Wavefront w fills LDS blocks 4w..4w+3 of each operand; a block is 8 rows x 8 chunks
+    // of 16 bytes, and lane l lands on row l/8, stored chunk l%8, which holds the logical
+    // chunk (l%8) ^ swizzle(row).  Rows beyond the matrix re-read its last row.
+    const uint16_t* ga[NBLK];
+    const uint16_t* gb[NBLK];
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) {
+        const int row = (wave * NBLK + i) * 8 + (lane >> 3);
+        const int kc = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
+        ga[i] = g.A + (int64_t)min(m0 + row, g.M - 1) * g.lda + kc * 8;
+        gb[i] = g.B + (int64_t)min(n0 + row, g.N - 1) * g.ldb + kc * 8;
+    }
+    auto fetch1 = [&](uint16_t* Ad, uint16_t* Bd, int k0, int i) {
+        __builtin_amdgcn_global_load_lds((gptr_t)(ga[i] + k0), (lptr_t)(Ad + (wave * NBLK + i) * 512), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + k0), (lptr_t)(Bd + (wave * NBLK + i) * 512), 16, 0, 0);
+    };
+    auto fetch = [&](uint16_t* Ad, uint16_t* Bd, int k0) {
+#pragma unroll
+        for (int i = 0; i < NBLK; ++i) fetch1(Ad, Bd, k0, i);
+    };
+
+    const int KT = g.K / BK;
+    // Operand fragments: set 0 and set 1 alternate between the four 16-wide k-steps of a tile.
+    bf16x8 af[2][MI], bfr[2][NI];
+    auto read_frags = [&](const uint16_t* Ac, const uint16_t* Bc, int kk, bf16x8 (&a)[MI], bf16x8 (&b)[NI]) {
+        const int kc = kk * 2 + (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+            a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Ac + lds_index(wm * WM + i * 32 + (lane & 31), kc)));
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+            b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Bc + lds_index(wn * WN + j * 32 + (lane & 31), kc)));
+    };
+    // the MFMAs of one step; the LDS reads of the next step are issued after the first NI of
+    // them, so that the wait in front of a step only covers reads that are a step old
+    auto mfmas = [&](const bf16x8 (&a)[MI], const bf16x8 (&b)[NI], int i0, int i1) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+    // One k-tile.  On entry set 0 holds step 0 of this tile (read after the previous barrier).
+    // The next tile lands in stage (An, Bn), last read before the previous barrier, while
+    // this one is multiplied; the reads of a step precede most MFMAs of the step before it,
+    // also across the barrier: the last step's MFMAs cover the first reads of the next
+    // tile, which all wavefronts issue at once when the barrier opens.
+    auto tile_step = [&](const uint16_t* Ac, const uint16_t* Bc, uint16_t* An, uint16_t* Bn, int kt) {
+        const bool more = kt + 1 < KT;
+        if (more) fetch(An, Bn, (kt + 1) * BK);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[0], bfr[0], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(Ac, Bc, 1, af[1], bfr[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[0], bfr[0], 1, MI);
+        mfmas(af[1], bfr[1], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(Ac, Bc, 2, af[0], bfr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[1], bfr[1], 1, MI);
+        mfmas(af[0], bfr[0], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(Ac, Bc, 3, af[1], bfr[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[0], bfr[0], 1, MI);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the next tile's chunks of this wavefront have landed
+        __syncthreads();                      // ... and everybody's; everybody is done reading this tile
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[1], bfr[1], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) read_frags(An, Bn, 0, af[0], bfr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[1], bfr[1], 1, MI);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    fetch(A0, B0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    read_frags(A0, B0, 0, af[0], bfr[0]);
+    for (int kt = 0; kt < KT; kt += 2) {
+        tile_step(A0, B0, A1, B1, kt);
+        if (kt + 1 < KT) tile_step(A1, B1, A0, B0, kt + 1);
+    }
+
+    static_for<MI * NI>([&](auto ij) {
+        constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
+        const int n = n0 + wn * WN + j * 32 + (lane & 31);
+        const int mb = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
+        static_for<16>([&](auto ee) {
+            constexpr int e = decltype(ee)::value;
+            epilogue_store(g, mb + 8 * (e >> 2) + (e & 3), n, acc[i][j][e]);
+        });
+    });
+}
+
 // ---- skinny: M <= 32 rows, B stored [N,K] -----------------------------------
 // out[m][n] = sum_k x[m][k] W[n][k] on MFMA 16x16x32 with the WEIGHTS as the
 // row operand: D[n][m] += W[n][k..k+31] x[m][k..k+31].  A workgroup owns 16*NB
@@ -640,7 +778,7 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
 
 constexpr int SKINNY_NB = 2;        // 16-column blocks per workgroup of the skinny kernels
 
-enum { V_SKINNY32 = 3, V_TILE64 = 10, V_TILE128 = 20, V_TILE256 = 30,
+enum { V_SKINNY32 = 3, V_TILE64 = 10, V_TILE128 = 20, V_TILE256 = 30, V_NT256 = 31,
        V_SKL4 = 40, V_SKL8 = 41, V_SKL16 = 42 };   // LDS-staged activations of at most 4 / 8 / 16 rows
 
 typedef void (*gemm_fn)(GemmArgs, AtomArgs);
@@ -665,7 +803,7 @@ static gemm_fn tile_fn(int tile, bool ta, bool tb, bool split)
 #undef PICKS
 }
 
-static int tile_threads(int variant) { return variant == 30 ? 512 : (variant < 10 || variant >= 40) ? SKINNY_WAVES * 64 : 256; }
+static int tile_threads(int variant) { return (variant == 30 || variant == 31) ? 512 : (variant < 10 || variant >= 40) ? SKINNY_WAVES * 64 : 256; }
 
 static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split)
 {
@@ -674,6 +812,7 @@ static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split)
     case V_SKL4: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<4, 2, 4, true> : (gemm_fn)gemm_skinny_lds_kernel<4, 2, 4, false>;
     case V_SKL8: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<8, 2, 4, true> : (gemm_fn)gemm_skinny_lds_kernel<8, 2, 4, false>;
     case V_SKL16: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<16, 2, 2, true> : (gemm_fn)gemm_skinny_lds_kernel<16, 2, 2, false>;
+    case V_NT256: return (gemm_fn)gemm_nt256_kernel<2, 4>;
     case V_TILE64: return tile_fn(64, ta, tb, split);
     case V_TILE128: return tile_fn(128, ta, tb, split);
     default: return tile_fn(256, ta, tb, split);
@@ -725,6 +864,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
     } else if (tile == 64 || tile == 128 || tile == 256) {
         if (split && tile == 256) return fail(LITHOS_EINVAL, "gemm: SPLIT_A is built for the 64 and 128 tiles only");
         variant = tile == 64 ? V_TILE64 : tile == 128 ? V_TILE128 : V_TILE256;
+        if (tile == 256 && !ta && tb && K % 64 == 0) variant = V_NT256;
         plan->grid = {(uint32_t)((N + tile - 1) / tile), (uint32_t)((M + tile - 1) / tile), 1};
     } else {
         return fail(LITHOS_EINVAL, "gemm: unknown tile selector %d", tile);

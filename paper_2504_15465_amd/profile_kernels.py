@@ -27,6 +27,7 @@ def main():
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--cus", type=int, default=256)
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--nt", action="store_true", help="gemm8192: B stored [N,K] (TRANS_B)")
     args = ap.parse_args()
 
     ctx = B.lithos_init(0, None)
@@ -43,7 +44,7 @@ def main():
         a_bits, b_bits = inputs.gemm_operands(n, n, n, seed=4)
         a, b = inputs.bits_to_torch(a_bits, "cuda"), inputs.bits_to_torch(b_bits, "cuda")
         c = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
-        op = B.gemm_op(a, b, c, n, n, n, tile=args.tile)
+        op = B.gemm_op(a, b, c, n, n, n, tile=args.tile, tb=args.nt)      # square: the same buffer serves as [N,K]
         grid, wg = B.lithos_op_grid(ctx, op)
         atom = 0 if args.what == "gemm8192" else args.cus * wg
         torch.cuda.synchronize()

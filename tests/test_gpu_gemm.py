@@ -70,6 +70,22 @@ def test_tiles_layouts_ragged_shapes(tile, ta, tb):
         assert bits_equal(c_atom, c_full)
 
 
+@pytest.mark.parametrize("m,n,k", [(520, 776, 320), (256, 256, 64), (300, 260, 128), (1, 8, 192)])
+def test_nt_256_tile_with_k_multiple_of_64(m, n, k):
+    """A [M,K] times B [N,K] with 256x256 tiles and K % 64 == 0 takes the kernel that loads
+    global memory straight into LDS: odd and even numbers of k-tiles, ragged M and N."""
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=77, tb=True)
+    ref = O.gemm(a_bits, b_bits, tb=True)
+    c_full, grid, _ = run_gemm(a_bits, b_bits, m, n, k, False, True, 256)
+    assert not torch.isnan(c_full).any()
+    assert rel_fro(c_full, ref) <= FRO_TOL
+    total = grid[0] * grid[1]
+    for atom_blocks in sorted({1, max(1, total - 1)}):
+        c_atom, _, cnt = run_gemm(a_bits, b_bits, m, n, k, False, True, 256, atom_blocks=atom_blocks, count=True)
+        assert cnt.cpu().tolist() == [1] * total
+        assert bits_equal(c_atom, c_full)
+
+
 def test_exactly_representable_data_matches_oracle_bit_for_bit():
     rng = np.random.default_rng(1)
     vals = np.array([1, -1, .5, -.5, 2, -2], np.float32)
@@ -123,17 +139,19 @@ def test_skinny_weight_streaming_gemm(m, n, k):
     assert grid_auto == grid and bits_equal(c, c_auto)
 
 
-def test_full_size_8192_cubed_sampled_rows():
+@pytest.mark.parametrize("tb", [True, False])
+def test_full_size_8192_cubed_sampled_rows(tb):
     """The benchmark's best-effort GEMM at full size, 256x256 tiles, in the
-    launch shape bench.py times (unatomized and cut in atoms of 256 blocks);
-    64 sampled full rows of C are checked against the oracle."""
+    launch shape bench.py times (weights stored [N,K]; unatomized and cut in
+    atoms of 256 blocks), and the [K,N] layout beside it; 64 sampled full rows
+    of C are checked against the oracle."""
     m = n = k = 8192
-    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=4)
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=4, tb=tb)
     a, b = dev_bits(a_bits), dev_bits(b_bits)
     c_full = nan_like((m, n), torch.float32)
     c_atom = nan_like((m, n), torch.float32)
-    op_full = B.gemm_op(a, b, c_full, m, n, k, tile=256)
-    op_atom = B.gemm_op(a, b, c_atom, m, n, k, tile=256)
+    op_full = B.gemm_op(a, b, c_full, m, n, k, tile=256, tb=tb)
+    op_atom = B.gemm_op(a, b, c_atom, m, n, k, tile=256, tb=tb)
     grid, _ = B.lithos_op_grid(ctx(), op_full)
     assert grid == (32, 32, 1)
     cnt = counters(1024)
@@ -148,7 +166,7 @@ def test_full_size_8192_cubed_sampled_rows():
     assert cnt.cpu().tolist() == [1] * 1024
     assert bits_equal(c_full, c_atom)
     rows = np.sort(np.random.default_rng(0).choice(m, 64, replace=False))
-    ref = O.gemm(a_bits[rows], b_bits)
+    ref = O.gemm(a_bits[rows], b_bits, tb=tb)
     assert rel_fro(c_full[torch.from_numpy(rows).cuda()], ref) <= FRO_TOL
 
 
