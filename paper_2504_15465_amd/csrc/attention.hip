@@ -345,14 +345,34 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, AtomArgs at
     const float* ml = ws + (int64_t)a.batch * a.n_kv * S * G * D;
     for (int i = threadIdx.x; i < G * D; i += 256) {
         const int h = i / D, d = i % D;
+        // eight splits at a time, their loads issued together (a split index beyond S re-reads the
+        // last split and is given weight 0); the sums still run in split order
+        const float2* mlr = reinterpret_cast<const float2*>(ml) + (int64_t)bg * S * G + h;     // split s at mlr[s * G]
+        const float* wsr = ws + ((int64_t)bg * S * G + h) * D + d;                               // split s at wsr[s * G * D]
         float gm = -INFINITY;
-        for (int s = 0; s < S; ++s) gm = fmaxf(gm, ml[(((int64_t)bg * S + s) * G + h) * 2]);
+        for (int s0 = 0; s0 < S; s0 += 8) {
+            float m8[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) m8[u] = mlr[(int64_t)min(s0 + u, S - 1) * G].x;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) gm = fmaxf(gm, m8[u]);
+        }
         float num = 0.0f, den = 0.0f;
-        for (int s = 0; s < S; ++s) {
-            const int64_t row = ((int64_t)bg * S + s) * G + h;
-            const float f = expf(ml[row * 2] - gm);               // 0 for a split without keys
-            num += ws[row * D + d] * f;
-            den += ml[row * 2 + 1] * f;
+        for (int s0 = 0; s0 < S; s0 += 8) {
+            float2 p8[8];
+            float o8[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t sc = min(s0 + u, S - 1);
+                p8[u] = mlr[sc * G];
+                o8[u] = wsr[sc * G * D];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float f = s0 + u < S ? expf(p8[u].x - gm) : 0.0f;     // 0 for a split without keys
+                num += o8[u] * f;
+                den += p8[u].y * f;
+            }
         }
         const float r = num / den;
         const int64_t idx = (int64_t)b * ((int64_t)a.n_q * D) + (g * G + h) * D + d;

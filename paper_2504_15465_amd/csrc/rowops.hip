@@ -263,6 +263,63 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(RowArgs a, AtomArgs atom)
         store_elem<OUT32>(a.y, off + c, load_elem<IN32>(a.x, off + c) * rinv * a.p0[c]);
 }
 
+// Register-resident variant (H % 4 == 0, H <= 16 * TPR): the row is read once with
+// 16-byte (fp32) or 8-byte (bf16) loads that are all in flight together.
+template <bool IN32, bool OUT32, int TPR>
+__global__ __launch_bounds__(256) void rmsnorm_vec_kernel(RowArgs a, AtomArgs atom)
+{
+    __shared__ float red[4];
+    constexpr int NV = 4;
+    const uint32_t L = atom_logical_block(atom);
+    constexpr int RPB = 256 / TPR;
+    const int64_t row = (int64_t)L * RPB + threadIdx.x / TPR;
+    const int t = threadIdx.x % TPR;
+    const bool live = row < a.rows;
+    const int64_t H = a.cols, off = row * H;
+    float v[NV][4];
+    float4 w[NV];
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t c = 4 * (t + (int64_t)j * TPR);
+        v[j][0] = v[j][1] = v[j][2] = v[j][3] = 0.0f;
+        w[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live && c < H) {
+            if constexpr (IN32) {
+                const float4 f = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.x) + off + c);
+                v[j][0] = f.x; v[j][1] = f.y; v[j][2] = f.z; v[j][3] = f.w;
+            } else {
+                const uint2 u = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(a.x) + off + c);
+                v[j][0] = __uint_as_float(u.x << 16); v[j][1] = __uint_as_float(u.x & 0xffff0000u);
+                v[j][2] = __uint_as_float(u.y << 16); v[j][3] = __uint_as_float(u.y & 0xffff0000u);
+            }
+            w[j] = *reinterpret_cast<const float4*>(a.p0 + c);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += v[j][e] * v[j][e];
+    const float ms = row_sum<TPR>(s, red) / (float)H;
+    const float rinv = 1.0f / sqrtf(ms + a.f0);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t c = 4 * (t + (int64_t)j * TPR);
+        if (live && c < H) {
+            const float y[4] = {v[j][0] * rinv * w[j].x, v[j][1] * rinv * w[j].y, v[j][2] * rinv * w[j].z, v[j][3] * rinv * w[j].w};
+            if constexpr (OUT32) {
+                *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + off + c) = make_float4(y[0], y[1], y[2], y[3]);
+            } else {
+                uint16_t h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16_bits(y[e]);
+                *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.y) + off + c) =
+                    make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+            }
+        }
+    }
+}
+
 // ---- softmax(scale * s) -----------------------------------------------------
 template <bool IN32, bool OUT32, int TPR>
 __global__ __launch_bounds__(256) void softmax_kernel(RowArgs a, AtomArgs atom)
@@ -385,6 +442,8 @@ int rowops_plan(const lithos_op_t& op, OpPlan* plan)
     case LITHOS_OP_RMSNORM:
         if (!op.in[1] || !op.out[0]) return fail(LITHOS_EINVAL, "rmsnorm: null weight or output");
         blocks = (rows + (256 / tpr_for(cols)) - 1) / (256 / tpr_for(cols));
+        if (cols % 4 == 0 && cols <= 16 * tpr_for(cols) && aligned16(op.in[0]) && aligned16(op.in[1]) && aligned16(op.out[0]))
+            plan->variant = 1;
         break;
     case LITHOS_OP_SOFTMAX:
         if (!op.out[0]) return fail(LITHOS_EINVAL, "softmax: null output");
@@ -449,7 +508,15 @@ int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& ato
         }
         break;
     case LITHOS_OP_RMSNORM:
-        if (tpr_for(a.cols) == 64) {
+        if (plan.variant == 1) {          // register-resident rows
+            if (tpr_for(a.cols) == 64) {
+                if (in32) { if (out32) L3(rmsnorm_vec_kernel, true, true, 64); else L3(rmsnorm_vec_kernel, true, false, 64); }
+                else      { if (out32) L3(rmsnorm_vec_kernel, false, true, 64); else L3(rmsnorm_vec_kernel, false, false, 64); }
+            } else {
+                if (in32) { if (out32) L3(rmsnorm_vec_kernel, true, true, 256); else L3(rmsnorm_vec_kernel, true, false, 256); }
+                else      { if (out32) L3(rmsnorm_vec_kernel, false, true, 256); else L3(rmsnorm_vec_kernel, false, false, 256); }
+            }
+        } else if (tpr_for(a.cols) == 64) {
             if (in32) { if (out32) L3(rmsnorm_kernel, true, true, 64); else L3(rmsnorm_kernel, true, false, 64); }
             else      { if (out32) L3(rmsnorm_kernel, false, true, 64); else L3(rmsnorm_kernel, false, false, 64); }
         } else {

@@ -61,14 +61,29 @@ def test_layernorm(rows, cols, in32, out32):
     assert bits_equal(y, ya)
 
 
-@pytest.mark.parametrize("rows,cols", [(8, 4096), (16, 14336), (3, 520)])
-def test_rmsnorm(rows, cols):
+@pytest.mark.parametrize("rows,cols", [(8, 4096), (16, 14336), (3, 520), (5, 1001), (70, 1024)])
+@pytest.mark.parametrize("in32,out32", [(True, False), (True, True), (False, False)])
+def test_rmsnorm(rows, cols, in32, out32):
+    """Rows that fit in registers (cols % 4 == 0, at most 4096) take the single-read kernel,
+    the others the two-pass one."""
     x32 = inputs.normal_f32((rows, cols), 4, 3.0)
+    if not in32:
+        x32 = O.bf16_to_f64(inputs.to_bf16_bits(x32)).astype(np.float32)
     w = inputs.normal_f32((cols,), 5, 0.1, 1.0)
     ref = O.rmsnorm(x32.astype(np.float64), w.astype(np.float64), 1e-5)
-    y = nan_like((rows, cols), torch.bfloat16)
-    launch(B.rmsnorm_op(torch.from_numpy(x32).cuda(), torch.from_numpy(w).cuda(), y, rows, cols, 1e-5))
-    bf16_close(y, ref)
+    x = torch.from_numpy(x32).cuda()
+    if not in32:
+        x = x.to(torch.bfloat16)
+    y = nan_like((rows, cols), torch.float32 if out32 else torch.bfloat16)
+    op = B.rmsnorm_op(x, torch.from_numpy(w).cuda(), y, rows, cols, 1e-5)
+    launch(op)
+    if out32:
+        assert np.abs(y.cpu().numpy().astype(np.float64) - ref).max() <= 2e-6 * max(1.0, np.abs(ref).max())
+    else:
+        bf16_close(y, ref)
+    ya = nan_like(y.shape, y.dtype)
+    launch(B.rmsnorm_op(x, torch.from_numpy(w).cuda(), ya, rows, cols, 1e-5), atom_blocks=2)
+    assert bits_equal(y, ya)
 
 
 @pytest.mark.parametrize("rows,cols", [(8, 4096), (300, 3072), (7, 1001)])
