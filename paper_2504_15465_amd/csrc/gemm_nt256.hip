@@ -1,0 +1,179 @@
+#include "gemm_common.hpp"
+
+namespace lithos {
+
+// ---- 256x256 tile, both operands k-contiguous, global -> LDS without registers ---
+// C = A B^T with A [M,K] and B [N,K] (TRANS_B), K a multiple of 64.  The k-tiles go
+// from global memory straight into LDS (global_load_lds_dwordx4: the 64 lanes of a
+// wavefront fill 1 KB of LDS in lane order, so each lane fetches the 16-byte chunk
+// that the swizzled layout wants at its position).  That frees the 32 staging
+// registers of the general kernel, which pay for a second set of operand fragments:
+// the LDS reads of step kk+1 are issued before the MFMAs of step kk.
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int WGM, int WGN, bool ST>
+__global__ __launch_bounds__(WGM * WGN * 64)
+void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
+{
+    static_assert(!ST || (WGM == 2 && WGN == 4), "the staged epilogue maps 32-row blocks to the four 64-row buffers");
+    constexpr int BM = 256, BN = 256, BK = 64, WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
+    constexpr int NBLK = 32 / (WGM * WGN);          // 1 KB blocks of each operand that a wavefront fetches
+    // four separate arrays, each addressed statically: the compiler can then tell that the
+    // LDS reads of one stage do not depend on the loads in flight into the other
+    __shared__ __attribute__((aligned(1024))) uint16_t A0[BM * BK];
+    __shared__ __attribute__((aligned(1024))) uint16_t A1[BM * BK];
+    __shared__ __attribute__((aligned(1024))) uint16_t B0[BN * BK];
+    __shared__ __attribute__((aligned(1024))) uint16_t B1[BN * BK];
+
+    const uint32_t L = atom_logical_block(atom);
+    const Block3 blk = atom_delinearize(L, atom);
+    uint32_t tm, tn;
+    tile_of_block((blk.z * atom.gy + blk.y) * atom.gx + blk.x, g.tiles_m, g.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // Wavefront w fills LDS blocks 4w..4w+3 of each operand; a block is 8 rows x 8 chunks
+    // of 16 bytes, and lane l lands on row l/8, stored chunk l%8, which holds the logical
+    // chunk (l%8) ^ swizzle(row).  Rows beyond the matrix re-read its last row.
+    const uint16_t* ga[NBLK];
+    const uint16_t* gb[NBLK];
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) {
+        const int row = (wave * NBLK + i) * 8 + (lane >> 3);
+        const int kc = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
+        ga[i] = g.A + (int64_t)min(m0 + row, g.M - 1) * g.lda + kc * 8;
+        gb[i] = g.B + (int64_t)min(n0 + row, g.N - 1) * g.ldb + kc * 8;
+    }
+    auto fetch1 = [&](uint16_t* Ad, uint16_t* Bd, int k0, int i) {
+        __builtin_amdgcn_global_load_lds((gptr_t)(ga[i] + k0), (lptr_t)(Ad + (wave * NBLK + i) * 512), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + k0), (lptr_t)(Bd + (wave * NBLK + i) * 512), 16, 0, 0);
+    };
+    auto fetch = [&](uint16_t* Ad, uint16_t* Bd, int k0) {
+#pragma unroll
+        for (int i = 0; i < NBLK; ++i) fetch1(Ad, Bd, k0, i);
+    };
+
+    const int KT = g.K / BK;
+    // Operand fragments: set 0 and set 1 alternate between the four 16-wide k-steps of a tile.
+    bf16x8 af[2][MI], bfr[2][NI];
+    auto read_frags = [&](const uint16_t* Ac, const uint16_t* Bc, int kk, bf16x8 (&a)[MI], bf16x8 (&b)[NI]) {
+        const int kc = kk * 2 + (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+            a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Ac + lds_index(wm * WM + i * 32 + (lane & 31), kc)));
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+            b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Bc + lds_index(wn * WN + j * 32 + (lane & 31), kc)));
+    };
+    // the MFMAs of one step; the LDS reads of the next step are issued after the first NI of
+    // them, so that the wait in front of a step only covers reads that are a step old
+    auto mfmas = [&](const bf16x8 (&a)[MI], const bf16x8 (&b)[NI], int i0, int i1) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                if constexpr (ST) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+                else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
+    };
+    // One k-tile.  On entry set 0 holds step 0 of this tile (read after the previous barrier).
+    // The next tile lands in stage (An, Bn), last read before the previous barrier, while
+    // this one is multiplied; the reads of a step precede most MFMAs of the step before it,
+    // also across the barrier: the last step's MFMAs cover the first reads of the next
+    // tile, which all wavefronts issue at once when the barrier opens.
+    auto tile_step = [&](const uint16_t* Ac, const uint16_t* Bc, uint16_t* An, uint16_t* Bn, int kt) {
+        const bool more = kt + 1 < KT;
+        if (more) fetch(An, Bn, (kt + 1) * BK);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[0], bfr[0], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(Ac, Bc, 1, af[1], bfr[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[0], bfr[0], 1, MI);
+        mfmas(af[1], bfr[1], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(Ac, Bc, 2, af[0], bfr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[1], bfr[1], 1, MI);
+        mfmas(af[0], bfr[0], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(Ac, Bc, 3, af[1], bfr[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[0], bfr[0], 1, MI);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the next tile's chunks of this wavefront have landed
+        __syncthreads();                      // ... and everybody's; everybody is done reading this tile
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[1], bfr[1], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) read_frags(An, Bn, 0, af[0], bfr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(af[1], bfr[1], 1, MI);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    fetch(A0, B0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    read_frags(A0, B0, 0, af[0], bfr[0]);
+    for (int kt = 0; kt < KT; kt += 2) {
+        tile_step(A0, B0, A1, B1, kt);
+        if (kt + 1 < KT) tile_step(A1, B1, A0, B0, kt + 1);
+    }
+
+    if constexpr (ST) {
+        // the four 32 KB buffers hold rows 0-63, 64-127, 128-191, 192-255 of the bf16 tile
+        if (m0 + BM <= g.M && n0 + BN <= g.N) {
+            __syncthreads();
+            static_for<MI * NI>([&](auto ij) {
+                constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
+                uint16_t* const st = wm == 0 ? (i < 2 ? A0 : A1) : (i < 2 ? B0 : B1);
+                stage_block<BN>(g, st, (i & 1) * 32 + (lane & 31), m0 + wm * WM + i * 32 + (lane & 31), wn * WN + j * 32,
+                                n0 + wn * WN + j * 32, acc[i][j], lane);
+            });
+            __syncthreads();
+            uint16_t* const C = reinterpret_cast<uint16_t*>(g.C);
+            const uint16_t* const src = wave < 2 ? A0 : wave < 4 ? A1 : wave < 6 ? B0 : B1;
+#pragma unroll 4
+            for (int it = 0; it < 16; ++it) {            // wavefront w stores rows 32w .. 32w+31, two per step
+                const int r = (wave & 1) * 32 + it * 2 + (lane >> 5), p = lane & 31;
+                const uint4 v = *reinterpret_cast<const uint4*>(src + stage_index<BN>(r, p));
+                *reinterpret_cast<uint4*>(C + (int64_t)(m0 + (wave >> 1) * 64 + r) * g.ldc + n0 + p * 8) = v;
+            }
+        } else {
+            static_for<MI * NI>([&](auto ij) {
+                constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
+                store_block_swapped(g, m0 + wm * WM + i * 32 + (lane & 31), n0 + wn * WN + j * 32, acc[i][j], lane);
+            });
+        }
+        return;
+    }
+
+    static_for<MI * NI>([&](auto ij) {
+        constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
+        const int n = n0 + wn * WN + j * 32 + (lane & 31);
+        const int mb = m0 + wm * WM + i * 32 + 4 * (lane >> 5);
+        static_for<16>([&](auto ee) {
+            constexpr int e = decltype(ee)::value;
+            epilogue_store(g, mb + 8 * (e >> 2) + (e & 3), n, acc[i][j][e]);
+        });
+    });
+}
+
+gemm_fn gemm_nt256_fn(bool st)
+{
+    return st ? (gemm_fn)gemm_nt256_kernel<2, 4, true> : (gemm_fn)gemm_nt256_kernel<2, 4, false>;
+}
+
+} // namespace lithos

@@ -1,0 +1,369 @@
+#include "gemm_common.hpp"
+
+namespace lithos {
+
+// ---- skinny: M <= 32 rows, B stored [N,K] -----------------------------------
+// out[m][n] = sum_k x[m][k] W[n][k] on MFMA 16x16x32 with the WEIGHTS as the
+// row operand: D[n][m] += W[n][k..k+31] x[m][k..k+31].  A workgroup owns 16*NB
+// output columns; its eight wavefronts split K in equal slices and their partial
+// tiles are added in wave order through LDS.  Every lane streams 16 bytes of
+// one weight row per step (64 contiguous bytes per row and step, rows walked
+// sequentially), so the weight matrix is read from HBM exactly once.
+// fp32 activations are fed exactly: x = hi + mid + lo with three bf16 values
+// (8 + 8 + 8 significant bits), three MFMAs per weight operand.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 pack_hi16(const float (&v)[8])
+{
+    // keep the upper 16 bits of each fp32 (truncation): a bf16 value
+    uint32_t w[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+        w[p] = (__float_as_uint(v[2 * p]) >> 16) | (__float_as_uint(v[2 * p + 1]) & 0xffff0000u);
+    return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+}
+
+// One register buffer of the skinny kernel: U k-steps of weights and activations.
+template <int MB, int NB, bool A32, int U>
+struct SkinnyBuf {
+    uint4 wv[U][NB];
+    uint4 xv[U][MB][A32 ? 2 : 1];
+
+    // step = index of the first of U consecutive 32-wide k-steps; the slice is walked
+    // cyclically from a per-workgroup rotation so that the workgroups, whose weight rows
+    // are a power-of-two stride apart, do not all address the same memory channels.
+    __device__ __forceinline__ void load(const GemmArgs& g, const uint16_t* const (&wrow)[NB], const bool (&mlive)[MB],
+                                         int step, int nsteps, int rot, int kbeg, int kend, int r16, int kg)
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // Loads are unconditional (addresses clamped into the matrix) and dead lanes are
+            // zeroed afterwards: straight-line loads let the hardware keep both register
+            // buffers' requests in flight, which branches around loads would prevent.
+            const int st = step + u;
+            const int k = kbeg + ((st + rot) % nsteps) * 32 + kg * 8;
+            const bool klive = st < nsteps && k < kend;
+            const int kc = min(k, g.K - 8);
+            const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const uint4 v = *reinterpret_cast<const uint4*>(wrow[j] + kc);
+                wv[u][j] = klive ? v : zero;
+            }
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                const int64_t row = min(i * 16 + r16, g.M - 1);
+                const bool live = klive && mlive[i];
+                if constexpr (A32) {
+                    const float* xp = reinterpret_cast<const float*>(g.A) + row * g.lda + kc;
+                    const uint4 v0 = *reinterpret_cast<const uint4*>(xp);
+                    const uint4 v1 = *reinterpret_cast<const uint4*>(xp + 4);
+                    xv[u][i][0] = live ? v0 : zero;
+                    xv[u][i][1] = live ? v1 : zero;
+                } else {
+                    const uint4 v0 = *reinterpret_cast<const uint4*>(g.A + row * g.lda + kc);
+                    xv[u][i][0] = live ? v0 : zero;
+                }
+            }
+        }
+    }
+
+    __device__ __forceinline__ void compute(f32x4 (&acc)[MB][NB]) const
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                if constexpr (A32) {
+                    float x[8], r1[8], r2[8];
+                    const uint4 a = xv[u][i][0], b = xv[u][i][1];
+                    const uint32_t raw[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        x[e] = __uint_as_float(raw[e]);
+                        r1[e] = x[e] - __uint_as_float(raw[e] & 0xffff0000u);               // exact
+                        r2[e] = r1[e] - __uint_as_float(__float_as_uint(r1[e]) & 0xffff0000u);  // exact, <= 8 bits
+                    }
+                    const bf16x8 xh = pack_hi16(x), xm = pack_hi16(r1), xl = pack_hi16(r2);
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) {
+                        const bf16x8 wf = __builtin_bit_cast(bf16x8, wv[u][j]);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xl, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xm, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xh, acc[i][j], 0, 0, 0);
+                    }
+                } else {
+                    const bf16x8 xf = __builtin_bit_cast(bf16x8, xv[u][i][0]);
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[u][j]), xf,
+                                                                             acc[i][j], 0, 0, 0);
+                }
+            }
+        }
+    }
+};
+
+
+template <int MB, int NB, bool A32>
+__global__ __launch_bounds__(SKINNY_WAVES * 64)
+void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
+{
+    constexpr int U = 2, KW = SKINNY_WAVES;     // two register buffers of U k-steps each
+    __shared__ __attribute__((aligned(16))) float red[KW][MB][NB][64][4];
+
+    const uint32_t L = atom_logical_block(atom);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r16 = lane & 15, kg = lane >> 4;
+    const int n0 = (int)L * 16 * NB;
+    // this wavefront's K range: equal slices rounded to whole 32-wide steps
+    const int kq = ((g.K + 32 * KW - 1) / (32 * KW)) * 32;
+    const int kbeg = wave * kq, kend = min(g.K, kbeg + kq);
+
+    f32x4 acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint16_t* wrow[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) wrow[j] = g.B + (int64_t)min(n0 + j * 16 + r16, g.N - 1) * g.ldb;
+    bool mlive[MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) mlive[i] = (i * 16 + r16) < g.M;
+
+    // software pipeline: the other buffer's loads are in flight while one is multiplied
+    const int nsteps = max(1, (kend - kbeg + 31) / 32);
+    const int rot = (int)((L * 7u + (uint32_t)wave * 3u) % (uint32_t)nsteps);
+    SkinnyBuf<MB, NB, A32, U> b0, b1;
+    b0.load(g, wrow, mlive, 0, nsteps, rot, kbeg, kend, r16, kg);
+    for (int st = 0; st < nsteps; st += 2 * U) {
+        b1.load(g, wrow, mlive, st + U, nsteps, rot, kbeg, kend, r16, kg);
+        b0.compute(acc);
+        b0.load(g, wrow, mlive, st + 2 * U, nsteps, rot, kbeg, kend, r16, kg);
+        b1.compute(acc);
+    }
+
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            *reinterpret_cast<f32x4*>(&red[wave][i][j][lane][0]) = acc[i][j];
+    __syncthreads();
+    if (wave == 0) {
+        // accumulator element e of a lane is D[n = 4*kg + e][m = r16]; slices are added in wave order
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = red[0][i][j][lane][e];
+#pragma unroll
+                    for (int w = 1; w < KW; ++w) v += red[w][i][j][lane][e];
+                    epilogue_store(g, i * 16 + r16, n0 + j * 16 + 4 * kg + e, v);
+                }
+    }
+}
+
+// ---- skinny GEMM, fp32 activations of at most 16 rows -------------------------
+// The kernel above loads activations straight into the MFMA operand layout,
+// which pads them to 16 rows: with 8 (or 4) live rows half (three quarters) of
+// those loads, and of the work of splitting fp32 into three bf16 values, is
+// spent on padding, and the padded activation loads take as many vector-memory
+// cycles as the weights.  Here a wavefront loads only the live rows of its
+// next K chunk (coalesced), splits them once and keeps the three bf16 planes in
+// its own piece of LDS, from which the operands are read; rows beyond MR read
+// one shared row of zeros.  Weights go global -> registers -> MFMA as before.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    // LDS operations of one wavefront complete in order; this only stops the compiler
+    // from moving reads of other lanes' data across the writes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int MR, int NB, int CH, bool A32>
+struct SkinnyChunk {
+    static constexpr int KC = CH * 32;              // k per chunk
+    static constexpr int EPL = A32 ? 4 : 8;         // activation elements per lane and 16-byte load
+    static constexpr int NX = MR * KC / (64 * EPL); // 16-byte loads per lane
+    static_assert(MR * KC % (64 * EPL) == 0, "a chunk of activations must fill whole 64-lane 16-byte loads");
+    uint4 wv[CH][NB];
+    uint4 xv[NX];
+
+    // kc0 = first k of the chunk; dead = chunk index beyond the slice
+    __device__ __forceinline__ void load(const GemmArgs& g, const uint16_t* const (&wrow)[NB], int kc0, int kend, bool dead,
+                                         int lane, int kg)
+    {
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int k = kc0 + u * 32 + kg * 8;
+            const bool klive = !dead && k < kend;
+            const int kc = min(k, g.K - 8);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const uint4 v = *reinterpret_cast<const uint4*>(wrow[j] + kc);
+                wv[u][j] = klive ? v : zero;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const int f = (i * 64 + lane) * EPL;
+            const int row = f / KC, k = kc0 + f % KC;
+            const bool live = !dead && row < g.M && k < kend;
+            const int64_t at = (int64_t)min(row, g.M - 1) * g.lda + min(k, g.K - EPL);
+            uint4 v;
+            if constexpr (A32) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(g.A) + at);
+            else v = *reinterpret_cast<const uint4*>(g.A + at);
+            xv[i] = live ? v : zero;
+        }
+    }
+
+    // x = hi + mid + lo exactly, each a bf16 value (upper 16 bits kept); planes are PL elements apart
+    template <int ROW, int PL>
+    __device__ __forceinline__ void stage(uint16_t* xs, int lane) const
+    {
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const int f = (i * 64 + lane) * EPL;
+            uint16_t* dst = xs + (f / KC) * ROW + f % KC;
+            if constexpr (!A32) {
+                *reinterpret_cast<uint4*>(dst) = xv[i];
+                continue;
+            }
+            const float x[4] = {__uint_as_float(xv[i].x), __uint_as_float(xv[i].y), __uint_as_float(xv[i].z), __uint_as_float(xv[i].w)};
+            uint32_t h[4], m[4], l[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                h[e] = __float_as_uint(x[e]) & 0xffff0000u;
+                const float r1 = x[e] - __uint_as_float(h[e]);                 // exact
+                m[e] = __float_as_uint(r1) & 0xffff0000u;
+                const float r2 = r1 - __uint_as_float(m[e]);                   // exact, at most 8 bits
+                l[e] = __float_as_uint(r2) & 0xffff0000u;
+            }
+            *reinterpret_cast<uint2*>(dst) = make_uint2((h[0] >> 16) | h[1], (h[2] >> 16) | h[3]);
+            *reinterpret_cast<uint2*>(dst + PL) = make_uint2((m[0] >> 16) | m[1], (m[2] >> 16) | m[3]);
+            *reinterpret_cast<uint2*>(dst + 2 * PL) = make_uint2((l[0] >> 16) | l[1], (l[2] >> 16) | l[3]);
+        }
+    }
+
+    template <int ROW, int PL>
+    __device__ __forceinline__ void compute(const uint16_t* xrow, int kg, f32x4 (&acc)[NB]) const
+    {
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const uint16_t* xp = xrow + u * 32 + kg * 8;
+            const bf16x8 xh = *reinterpret_cast<const bf16x8*>(xp);
+            if constexpr (A32) {
+                const bf16x8 xm = *reinterpret_cast<const bf16x8*>(xp + PL);
+                const bf16x8 xl = *reinterpret_cast<const bf16x8*>(xp + 2 * PL);
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const bf16x8 wf = __builtin_bit_cast(bf16x8, wv[u][j]);
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xl, acc[j], 0, 0, 0);
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xm, acc[j], 0, 0, 0);
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xh, acc[j], 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[u][j]), xh, acc[j], 0, 0, 0);
+            }
+        }
+    }
+};
+
+template <int MR, int NB, int CH, bool A32>
+__global__ __launch_bounds__(SKINNY_WAVES * 64)
+void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
+{
+    constexpr int KW = SKINNY_WAVES;
+    constexpr int KC = CH * 32;
+    constexpr int ROW = KC + 8;                      // padded row: 16 rows read 16 B each without bank conflicts
+    constexpr int PL = (MR + 1) * ROW;               // one plane: MR rows and the row of zeros
+    constexpr int NPL = A32 ? 3 : 1;                 // bf16 activations need no splitting
+    constexpr int XBYTES = KW * NPL * PL * 2;
+    constexpr int RBYTES = KW * NB * 64 * 16;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[XBYTES > RBYTES ? XBYTES : RBYTES];
+
+    const uint32_t L = atom_logical_block(atom);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r16 = lane & 15, kg = lane >> 4;
+    const int n0 = (int)L * 16 * NB;
+    const int kq = ((g.K + 32 * KW - 1) / (32 * KW)) * 32;
+    const int kbeg = wave * kq, kend = min(g.K, kbeg + kq);
+
+    uint16_t* xs = reinterpret_cast<uint16_t*>(smem) + wave * NPL * PL;
+    for (int t = lane; t < NPL * (ROW / 4); t += 64) // the row of zeros of each plane
+        *reinterpret_cast<uint2*>(xs + (t / (ROW / 4)) * PL + MR * ROW + (t % (ROW / 4)) * 4) = make_uint2(0, 0);
+    const uint16_t* xrow = xs + min(r16, MR) * ROW;
+
+    f32x4 acc[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint16_t* wrow[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) wrow[j] = g.B + (int64_t)min(n0 + j * 16 + r16, g.N - 1) * g.ldb + 0;
+
+    // chunks are walked cyclically from a per-workgroup start so that workgroups, whose weight
+    // rows are a power-of-two stride apart, do not address the same memory channels together
+    const int nch = max(1, (kend - kbeg + KC - 1) / KC);
+    int ci = (int)((L * 7u + (uint32_t)wave * 3u) % (uint32_t)nch);
+    auto next_chunk = [&](int& kc0) { kc0 = kbeg + ci * KC; ci = ci + 1 == nch ? 0 : ci + 1; };
+
+    SkinnyChunk<MR, NB, CH, A32> c0, c1;
+    int kc0;
+    next_chunk(kc0);
+    c0.load(g, wrow, kc0, kend, false, lane, kg);
+    c0.template stage<ROW, PL>(xs, lane);
+    wave_lds_sync();
+    for (int c = 0; c < nch; c += 2) {
+        next_chunk(kc0);
+        c1.load(g, wrow, kc0, kend, c + 1 >= nch, lane, kg);
+        c0.template compute<ROW, PL>(xrow, kg, acc);
+        wave_lds_sync();
+        c1.template stage<ROW, PL>(xs, lane);
+        wave_lds_sync();
+        next_chunk(kc0);
+        c0.load(g, wrow, kc0, kend, c + 2 >= nch, lane, kg);
+        c1.template compute<ROW, PL>(xrow, kg, acc);
+        wave_lds_sync();
+        c0.template stage<ROW, PL>(xs, lane);
+        wave_lds_sync();
+    }
+
+    __syncthreads();                                  // the reduction buffer overlays the activations
+    float (*red)[NB][64][4] = reinterpret_cast<float (*)[NB][64][4]>(smem);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) *reinterpret_cast<f32x4*>(&red[wave][j][lane][0]) = acc[j];
+    __syncthreads();
+    if (wave == 0) {
+        // accumulator element e of a lane is D[n = 4*kg + e][m = r16]; slices are added in wave order
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float v = red[0][j][lane][e];
+#pragma unroll
+                for (int w = 1; w < KW; ++w) v += red[w][j][lane][e];
+                epilogue_store(g, r16, n0 + j * 16 + 4 * kg + e, v);
+            }
+    }
+}
+
+gemm_fn gemm_skinny_fn(int variant, bool a32)
+{
+    switch (variant) {
+    case V_SKL4: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<4, 2, 4, true> : (gemm_fn)gemm_skinny_lds_kernel<4, 2, 4, false>;
+    case V_SKL8: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<8, 2, 4, true> : (gemm_fn)gemm_skinny_lds_kernel<8, 2, 4, false>;
+    case V_SKL16: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<16, 2, 2, true> : (gemm_fn)gemm_skinny_lds_kernel<16, 2, 2, false>;
+    default: return a32 ? (gemm_fn)gemm_skinny_kernel<2, SKINNY_NB, true> : (gemm_fn)gemm_skinny_kernel<2, SKINNY_NB, false>;
+    }
+}
+
+} // namespace lithos

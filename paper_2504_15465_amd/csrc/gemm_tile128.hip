@@ -1,0 +1,12 @@
+// 128x128-tile instances of the LDS-staged MFMA GEMM.
+#include "gemm_tile.hpp"
+
+namespace lithos {
+
+gemm_fn gemm_tile128_fn(bool ta, bool tb, bool split, bool st)
+{
+    if (split) return LITHOS_TILE_PICK_SPLIT(128);
+    return LITHOS_TILE_PICK(128, 2, 2);
+}
+
+} // namespace lithos
