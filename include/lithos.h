@@ -51,10 +51,12 @@ enum {
     LITHOS_OP_ROPE_KV   = 8,  /* rotary embedding of q and k (rotate-half) + append k,v to the cache */
     LITHOS_OP_SILU_MUL  = 9,  /* silu(gate) * up on a packed [rows, 2F] tensor */
     LITHOS_OP_SPIN      = 10, /* test kernel: every block spins a fixed number of clock ticks */
-    LITHOS_OP_ATTN_MERGE = 11 /* second step of a split ATTN_DEC: merges the key ranges' partial softmaxes */
+    LITHOS_OP_ATTN_MERGE = 11, /* second step of a split ATTN_DEC: merges the key ranges' partial softmaxes */
+    LITHOS_OP_SUM_SLICES = 12  /* second step of a K-sliced GEMM: adds the fp32 partial planes in slice order */
 };
 
 #define LITHOS_ATTN_MAX_SPLITS 64
+#define LITHOS_GEMM_MAX_SLICES 64
 
 /* flags (meaning depends on the kind, see the table below) */
 #define LITHOS_F_TRANS_A   (1u << 0)   /* A is stored [K,M] */
@@ -77,7 +79,17 @@ enum {
  * One operator instance.  Unused fields are zero.
  *
  * kind        dim[]                              in[] / out[]                         ld[] / fparam[]
- * GEMM        M,N,K                              A,B,bias(f32),residual(f32) / C      lda,ldb,ldc,ldr
+ * GEMM        M,N,K,[a_plane,c_plane,slices,     A,B,bias(f32),residual(f32) / C      lda,ldb,ldc,ldr
+ *             slice_plane]
+ *             slices (dim[5]) > 1 cuts K into that many ranges of whole 64-wide k-tiles (balanced:
+ *             range z holds the k-tiles [z*KT/S, (z+1)*KT/S)); the logical grid gets z = slices and
+ *             block (x,y,z) writes its fp32 partial tile to plane z of out[0], dim[6] (>= M*ldc)
+ *             elements after plane z-1.  Needs OUT_F32 and no epilogue flag; a wide K with few output
+ *             tiles fills the chip that way.  SUM_SLICES on the same queue then adds the planes in
+ *             slice order and applies the epilogue, so the result does not depend on how either
+ *             launch was cut into atoms.
+ * SUM_SLICES  rows,cols,slices,slice_plane       planes(f32),bias(f32),residual(f32) / y   ld0=row stride of the planes,
+ *             y = act(sum_z plane_z + bias) + residual; BIAS, GELU, RESIDUAL, OUT_F32 as for GEMM          ld1=of y, ld2=of residual
  * BIAS_ACT    rows,cols                          x,bias(f32) / y
  * LAYERNORM   rows,H                             x,gamma(f32),beta(f32) / y,[y_bf16]   fparam0=eps
  * SOFTMAX     rows,n                             s / p                                fparam0=scale
@@ -188,6 +200,13 @@ int lithos_probe_partition(lithos_ctx_t* ctx, const lithos_partition_t* p, uint3
 /* Logical grid of an operator and how many of its workgroups fit on one CU. */
 int lithos_op_grid(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3* grid_out,
                    uint32_t* wg_per_cu_out);
+
+/* For a GEMM whose output has too few tiles to fill `n_cus` compute units (a weight gradient:
+ * small M x N, long K): the tile selector and the number of K slices (lithos_op_t dim[5]) that
+ * put about one workgroup on every CU.  slices_out = 1: leave the GEMM whole.  Only M, N, K and
+ * the flags of `op` are read; nothing is launched.  The caller then provides the fp32 planes
+ * (slices * M * ldc floats) and follows the GEMM with SUM_SLICES. */
+int lithos_gemm_split_hint(const lithos_op_t* op, int32_t n_cus, int32_t* tile_out, int32_t* slices_out);
 
 /* Run `op` as ceil(total/atom_blocks) launches, atom i covering logical
  * blocks [i*atom_blocks, min((i+1)*atom_blocks, total)) of the grid numbered

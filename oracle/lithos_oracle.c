@@ -138,6 +138,19 @@ int lo_gemm_rowsweep(int ta, int64_t M, int64_t N, int64_t K,
     return 0;
 }
 
+/* K cut into ranges: C = sum_z A[:, K_z] B[K_z, :].  The planes hold the partial
+ * products of the ranges; they are added in range order, plane 0 first. */
+int lo_sum_slices(int64_t slices, int64_t n, const double *planes, double *out)
+{
+    if (slices < 1 || n < 0) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        double s = planes[i];
+        for (int64_t z = 1; z < slices; ++z) s += planes[z * n + i];
+        out[i] = s;
+    }
+    return 0;
+}
+
 /* -------------------------------------------------------- bias + GELU --- */
 
 /* exact (erf) GELU: g(u) = u/2 * (1 + erf(u / sqrt 2)) */

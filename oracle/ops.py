@@ -140,6 +140,22 @@ def gelu(u: float) -> float:
     return float(lib().lo_gelu(_dbl(u)))
 
 
+def k_slice_bounds(k: int, slices: int, ktile: int = 64):
+    """Balanced cut of K into ``slices`` ranges of whole ``ktile``-wide steps:
+    range z holds the steps [z*KT/S, (z+1)*KT/S) of the KT = ceil(K/ktile) steps."""
+    kt = -(-k // ktile)
+    return [(min(k, (z * kt // slices) * ktile), min(k, ((z + 1) * kt // slices) * ktile)) for z in range(slices)]
+
+
+def sum_slices(planes) -> np.ndarray:
+    """Sum of the partial products of a GEMM whose K was cut into ranges, plane 0 first."""
+    p, pp = _d(planes)
+    out = np.empty(p.shape[1:], dtype=np.float64)
+    rc = lib().lo_sum_slices(_i64(p.shape[0]), _i64(out.size), pp, out.ctypes.data_as(_pd))
+    assert rc == 0
+    return out
+
+
 def bias_act(x, bias=None, gelu: bool = True) -> np.ndarray:
     """y = g(x + bias) (g = erf-GELU, or identity when ``gelu`` is False)."""
     a, pa = _d(x)

@@ -20,7 +20,7 @@ OK, EINVAL, EHIP, EMASK, ESTATE, ELIMIT = 0, -1, -2, -3, -4, -5
 MASK_WORDS = 8
 MAX_SWEEP = 64
 
-OP_GEMM, OP_BIAS_ACT, OP_LAYERNORM, OP_SOFTMAX, OP_ATTN_ENC, OP_ATTN_DEC, OP_RMSNORM, OP_ROPE_KV, OP_SILU_MUL, OP_SPIN, OP_ATTN_MERGE = range(1, 12)
+OP_GEMM, OP_BIAS_ACT, OP_LAYERNORM, OP_SOFTMAX, OP_ATTN_ENC, OP_ATTN_DEC, OP_RMSNORM, OP_ROPE_KV, OP_SILU_MUL, OP_SPIN, OP_ATTN_MERGE, OP_SUM_SLICES = range(1, 13)
 ATTN_MAX_SPLITS = 64
 F_TRANS_A, F_TRANS_B, F_BIAS, F_GELU, F_RESIDUAL, F_OUT_F32, F_IN_F32, F_SPLIT_A, F_OUT_SPLIT = (1 << i for i in range(9))
 TILE_AUTO, TILE_SKINNY, TILE_64, TILE_128, TILE_256 = 0, 1, 64, 128, 256
@@ -79,7 +79,7 @@ EXPORTS = [
     "lithos_init", "lithos_shutdown", "lithos_device_info", "lithos_last_error",
     "lithos_make_mask", "lithos_create_partition", "lithos_destroy_partition", "lithos_partition_cus",
     "lithos_partition_stream", "lithos_probe_partition", "lithos_partitions_coupled",
-    "lithos_op_grid", "lithos_launch_atomized", "lithos_launch_atom", "lithos_partition_sync",
+    "lithos_op_grid", "lithos_gemm_split_hint", "lithos_launch_atomized", "lithos_launch_atom", "lithos_partition_sync",
     "lithos_debug_block_counters", "lithos_rightsize", "lithos_time_launch",
     "lithos_tenant_create", "lithos_tenant_destroy", "lithos_submit", "lithos_sync_mark", "lithos_sync",
     "lithos_poll", "lithos_tenant_stats",
@@ -146,8 +146,9 @@ def make_op(kind, dims=(), flags=0, tile=0, ld=(), fparam=(), inputs=(), outputs
 
 
 def gemm_op(a, b, c, m, n, k, ta=False, tb=False, bias=None, gelu=False, residual=None, tile=0,
-            lda=None, ldb=None, ldc=None, ldr=None, op_id=0, a_split=False, c_split=False) -> Op:
-    """``a_split``: ``a`` is a [2, M, K] bf16 pair (hi, lo planes); ``c_split``: ``c`` is a [2, M, N] pair."""
+            lda=None, ldb=None, ldc=None, ldr=None, op_id=0, a_split=False, c_split=False, k_slices=0, slice_plane=None) -> Op:
+    """``a_split``: ``a`` is a [2, M, K] bf16 pair (hi, lo planes); ``c_split``: ``c`` is a [2, M, N] pair;
+    ``k_slices`` > 1: ``c`` is an fp32 [k_slices, M, N] stack of partial planes for ``sum_slices_op``."""
     flags = (F_TRANS_A if ta else 0) | (F_TRANS_B if tb else 0) | (F_BIAS if bias is not None else 0)
     flags |= (F_GELU if gelu else 0) | (F_RESIDUAL if residual is not None else 0)
     if isinstance(c, torch.Tensor) and c.dtype == torch.float32:
@@ -159,8 +160,22 @@ def gemm_op(a, b, c, m, n, k, ta=False, tb=False, bias=None, gelu=False, residua
     ldc = ldc if ldc is not None else n
     ldr = ldr if ldr is not None else n
     flags |= (F_SPLIT_A if a_split else 0) | (F_OUT_SPLIT if c_split else 0)
-    return make_op(OP_GEMM, (m, n, k, m * lda if a_split else 0, m * ldc if c_split else 0), flags, tile,
+    if k_slices > 1 and slice_plane is None:
+        slice_plane = m * ldc
+    return make_op(OP_GEMM, (m, n, k, m * lda if a_split else 0, m * ldc if c_split else 0, k_slices, slice_plane or 0), flags, tile,
                    (lda, ldb, ldc, ldr), (), (a, b, bias, residual), (c,), op_id)
+
+
+def sum_slices_op(planes, y, rows, cols, slices, bias=None, gelu=False, residual=None, slice_plane=None,
+                  ldx=None, ldy=None, ldr=None, op_id=0) -> Op:
+    """Second step of a K-sliced GEMM: ``y = act(sum_z planes[z] + bias) + residual``, planes added in slice order."""
+    flags = (F_BIAS if bias is not None else 0) | (F_GELU if gelu else 0) | (F_RESIDUAL if residual is not None else 0)
+    if isinstance(y, torch.Tensor) and y.dtype == torch.float32:
+        flags |= F_OUT_F32
+    ldx = ldx if ldx is not None else cols
+    return make_op(OP_SUM_SLICES, (rows, cols, slices, slice_plane if slice_plane is not None else rows * ldx), flags,
+                   ld=(ldx, ldy if ldy is not None else cols, ldr if ldr is not None else cols),
+                   inputs=(planes, bias, residual), outputs=(y,), op_id=op_id)
 
 
 def bias_act_op(x, y, rows, cols, bias=None, gelu=True, op_id=0) -> Op:
@@ -300,6 +315,13 @@ def lithos_op_grid(ctx, op: Op):
     w = C.c_uint32()
     _check(lib().lithos_op_grid(ctx, C.byref(op), C.byref(g), C.byref(w)))
     return (g.x, g.y, g.z), w.value
+
+
+def lithos_gemm_split_hint(op: Op, n_cus=256):
+    """(tile, k_slices) that fill ``n_cus`` compute units; k_slices == 1: leave the GEMM whole."""
+    tile, slices = C.c_int32(0), C.c_int32(0)
+    _check(lib().lithos_gemm_split_hint(C.byref(op), int(n_cus), C.byref(tile), C.byref(slices)))
+    return tile.value, slices.value
 
 
 def lithos_launch_atomized(ctx, op: Op, grid=(0, 0, 0), atom_blocks=0, part=None, stream=None):

@@ -23,9 +23,12 @@ namespace lithos {
 static int tile_threads(int variant) { return (variant == 30 || variant == 31) ? 512 : (variant < 10 || variant >= 40) ? SKINNY_WAVES * 64 : 256; }
 
 // full bf16 tiles can leave through LDS when whole 16-byte pieces of C rows are addressable
+// (fp32 tiles of the same kernels are stored from registers, 16 bytes per lane)
 static bool staged_epilogue(const lithos_op_t& op)
 {
-    return !(op.flags & (LITHOS_F_OUT_F32 | LITHOS_F_OUT_SPLIT | LITHOS_F_SPLIT_A)) && op.ld[2] % 8 == 0 && aligned16(op.out[0]);
+    if (op.flags & (LITHOS_F_OUT_SPLIT | LITHOS_F_SPLIT_A)) return false;
+    if (op.flags & LITHOS_F_OUT_F32) return op.ld[2] % 4 == 0 && op.dim[6] % 4 == 0 && aligned16(op.out[0]);
+    return op.ld[2] % 8 == 0 && aligned16(op.out[0]);
 }
 
 static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split, bool st)
@@ -64,11 +67,19 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         return fail(LITHOS_EINVAL, "gemm: SPLIT_A needs bf16 A, no TRANS_A and a plane stride (dim[3]) that is a positive multiple of 8");
     if (out_split && ((op.flags & LITHOS_F_OUT_F32) || op.dim[4] <= 0))
         return fail(LITHOS_EINVAL, "gemm: OUT_SPLIT needs a bf16 output and a positive plane stride (dim[4])");
+    const int64_t slices = op.dim[5];
+    if (slices < 0 || slices > LITHOS_GEMM_MAX_SLICES) return fail(LITHOS_EINVAL, "gemm: K slices (dim[5]) must be in [0, %d]", LITHOS_GEMM_MAX_SLICES);
+    if (slices > 1) {
+        if (!(op.flags & LITHOS_F_OUT_F32) || (op.flags & (LITHOS_F_BIAS | LITHOS_F_GELU | LITHOS_F_RESIDUAL | LITHOS_F_OUT_SPLIT | LITHOS_F_IN_F32)))
+            return fail(LITHOS_EINVAL, "gemm: K slices write plain fp32 partial planes (OUT_F32, no epilogue flags); SUM_SLICES applies the epilogue");
+        if (op.dim[6] < M * ldc) return fail(LITHOS_EINVAL, "gemm: slice plane stride (dim[6]) smaller than M*ldc");
+        if (slices > (K + 63) / 64) return fail(LITHOS_EINVAL, "gemm: more K slices than 64-wide k-tiles");
+    }
     int tile = op.tile;
     if (a32 && !(M <= 32 && tb && !ta && (tile == 0 || tile == LITHOS_TILE_SKINNY)))
         return fail(LITHOS_EINVAL, "gemm: fp32 activations (IN_F32) are only taken by the skinny kernel (M <= 32, TRANS_B)");
     if (tile == 0) {
-        if (M <= 32 && tb && !ta) tile = LITHOS_TILE_SKINNY;
+        if (M <= 32 && tb && !ta && slices <= 1) tile = LITHOS_TILE_SKINNY;
         else if (!split && ((M + 255) / 256) * ((N + 255) / 256) >= 256) tile = 256;
         else if (((M + 127) / 128) * ((N + 127) / 128) >= 128) tile = 128;
         else tile = 64;
@@ -76,6 +87,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
     int variant;
     if (tile == LITHOS_TILE_SKINNY) {
         if (split) return fail(LITHOS_EINVAL, "gemm: the skinny kernel takes fp32 activations instead of SPLIT_A");
+        if (slices > 1) return fail(LITHOS_EINVAL, "gemm: the skinny kernel splits K inside the workgroup; K slices need a tile kernel");
         if (M > 32 || !tb || ta) return fail(LITHOS_EINVAL, "gemm: the skinny kernel needs M <= 32, TRANS_B and no TRANS_A");
         if (a32 && (lda % 4)) return fail(LITHOS_EINVAL, "gemm: fp32 activations need lda %% 4 == 0");
         variant = V_SKINNY32;
@@ -85,11 +97,11 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         if (split && tile == 256) return fail(LITHOS_EINVAL, "gemm: SPLIT_A is built for the 64 and 128 tiles only");
         variant = tile == 64 ? V_TILE64 : tile == 128 ? V_TILE128 : V_TILE256;
         if (tile == 256 && !ta && tb && K % 64 == 0) variant = V_NT256;
-        plan->grid = {(uint32_t)((N + tile - 1) / tile), (uint32_t)((M + tile - 1) / tile), 1};
+        plan->grid = {(uint32_t)((N + tile - 1) / tile), (uint32_t)((M + tile - 1) / tile), (uint32_t)(slices > 1 ? slices : 1)};
     } else {
         return fail(LITHOS_EINVAL, "gemm: unknown tile selector %d", tile);
     }
-    plan->total = plan->grid.x * plan->grid.y;
+    plan->total = plan->grid.x * plan->grid.y * plan->grid.z;
     plan->threads = tile_threads(variant);
     plan->variant = variant;
     int occ = 0;
@@ -112,6 +124,7 @@ int gemm_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     g.flags = op.flags;
     g.tiles_m = plan.grid.y; g.tiles_n = plan.grid.x;
     g.a_plane = op.dim[3]; g.c_plane = op.dim[4];
+    g.k_slices = (int)op.dim[5]; g.c_slice = op.dim[6];
     gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B, op.flags & LITHOS_F_IN_F32,
                             op.flags & LITHOS_F_SPLIT_A, staged_epilogue(op));
     LITHOS_HIP(launch_kernel(fn, dim3(atom.n), dim3(plan.threads), s, g, atom));

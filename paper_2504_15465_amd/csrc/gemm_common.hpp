@@ -22,7 +22,18 @@ struct GemmArgs {
     uint32_t tiles_m, tiles_n;
     int64_t a_plane;     // SPLIT_A: elements between the hi and the lo plane of A
     int64_t c_plane;     // OUT_SPLIT: elements between the hi and the lo plane of C
+    int k_slices;        // > 1: logical block z computes k-tiles [z*KT/S, (z+1)*KT/S) into fp32 plane z of C
+    int64_t c_slice;     // elements between the planes of consecutive K slices
 };
+
+// K slices (the logical grid's z axis): slice z of S owns the k-tiles [z*KT/S, (z+1)*KT/S),
+// a balanced cut that depends on nothing but z, so a slice's sum is the same in every launch.
+__device__ __forceinline__ void slice_ktiles(const GemmArgs& g, uint32_t z, int KT, int& kt0, int& kt1)
+{
+    if (g.k_slices <= 1) { kt0 = 0; kt1 = KT; return; }
+    kt0 = (int)(((int64_t)z * KT) / g.k_slices);
+    kt1 = (int)(((int64_t)(z + 1) * KT) / g.k_slices);
+}
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
 {
@@ -116,6 +127,26 @@ __device__ __forceinline__ void stage_block(const GemmArgs& g, uint16_t* st, int
         }
         *reinterpret_cast<uint2*>(st + stage_index<BN>(r, nl >> 3) + (nl & 4)) =
             make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+    });
+}
+
+// the same block of a full fp32 tile: 16 bytes (four columns) per lane and store
+__device__ __forceinline__ void store_block_swapped_f32(const GemmArgs& g, float* C, int m, int n_glob, const f32x16& acc, int lane)
+{
+    const bool plain = !(g.flags & (LITHOS_F_BIAS | LITHOS_F_GELU | LITHOS_F_RESIDUAL));   // uniform
+    static_for<4>([&](auto qq) {
+        constexpr int q = decltype(qq)::value;
+        const int n = n_glob + 8 * q + 4 * (lane >> 5);
+        float v[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        if (!plain) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (g.flags & LITHOS_F_BIAS) v[t] += g.bias[n + t];
+                if (g.flags & LITHOS_F_GELU) v[t] = gelu_erf(v[t]);
+                if (g.flags & LITHOS_F_RESIDUAL) v[t] += g.resid[(int64_t)m * g.ldr + n + t];
+            }
+        }
+        *reinterpret_cast<float4*>(C + (int64_t)m * g.ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
     });
 }
 

@@ -29,7 +29,7 @@ void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
     const uint32_t L = atom_logical_block(atom);
     const Block3 blk = atom_delinearize(L, atom);
     uint32_t tm, tn;
-    tile_of_block((blk.z * atom.gy + blk.y) * atom.gx + blk.x, g.tiles_m, g.tiles_n, tm, tn);
+    tile_of_block(blk.y * atom.gx + blk.x, g.tiles_m, g.tiles_n, tm, tn);   // blk.z is the K slice
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -64,7 +64,9 @@ void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
         for (int i = 0; i < NBLK; ++i) fetch1(Ad, Bd, k0, i);
     };
 
-    const int KT = g.K / BK;
+    int kt0, KT;                                    // this block's k-tiles are [kt0, KT)
+    slice_ktiles(g, blk.z, g.K / BK, kt0, KT);
+    if (g.k_slices > 1) g.C = reinterpret_cast<float*>(g.C) + (int64_t)blk.z * g.c_slice;
     // Operand fragments: set 0 and set 1 alternate between the four 16-wide k-steps of a tile.
     bf16x8 af[2][MI], bfr[2][NI];
     auto read_frags = [&](const uint16_t* Ac, const uint16_t* Bc, int kk, bf16x8 (&a)[MI], bf16x8 (&b)[NI]) {
@@ -123,18 +125,24 @@ void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    fetch(A0, B0, 0);
+    if (kt0 < KT) fetch(A0, B0, kt0 * BK);
     __builtin_amdgcn_s_waitcnt(0x0f70);
     __syncthreads();
-    read_frags(A0, B0, 0, af[0], bfr[0]);
-    for (int kt = 0; kt < KT; kt += 2) {
+    if (kt0 < KT) read_frags(A0, B0, 0, af[0], bfr[0]);
+    for (int kt = kt0; kt < KT; kt += 2) {
         tile_step(A0, B0, A1, B1, kt);
         if (kt + 1 < KT) tile_step(A1, B1, A0, B0, kt + 1);
     }
 
     if constexpr (ST) {
         // the four 32 KB buffers hold rows 0-63, 64-127, 128-191, 192-255 of the bf16 tile
-        if (m0 + BM <= g.M && n0 + BN <= g.N) {
+        if (m0 + BM <= g.M && n0 + BN <= g.N && (g.flags & LITHOS_F_OUT_F32)) {
+            static_for<MI * NI>([&](auto ij) {
+                constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
+                store_block_swapped_f32(g, reinterpret_cast<float*>(g.C), m0 + wm * WM + i * 32 + (lane & 31),
+                                        n0 + wn * WN + j * 32, acc[i][j], lane);
+            });
+        } else if (m0 + BM <= g.M && n0 + BN <= g.N) {
             __syncthreads();
             static_for<MI * NI>([&](auto ij) {
                 constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;

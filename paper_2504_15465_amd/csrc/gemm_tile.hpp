@@ -95,8 +95,11 @@ struct TileStage {
 // SPLIT: A is a pair of bf16 planes (hi, lo) whose sum carries ~16 significant
 // bits of the activation; both planes are multiplied with the same B operand.
 // ST: full bf16 tiles leave through LDS (operands exchanged in the MFMA, see stage_block).
+// Registers are capped so that 256x256 tiles keep two wavefronts per SIMD (one 8-wave workgroup
+// per CU), 128x128 tiles three workgroups and 64x64 tiles four: left alone, the compiler spends
+// the whole register file on hoisted epilogue addresses and halves the occupancy.
 template <int BM, int BN, int WGM, int WGN, bool TA, bool TB, bool SPLIT, bool ST>
-__global__ __launch_bounds__(WGM * WGN * 64)
+__global__ __launch_bounds__(WGM * WGN * 64, BM >= 256 ? 2 : BM >= 128 ? (SPLIT ? 2 : 3) : 4)
 void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 {
     constexpr int T = WGM * WGN * 64, BK = 64;
@@ -112,7 +115,7 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
     const uint32_t L = atom_logical_block(atom);
     const Block3 blk = atom_delinearize(L, atom);
     uint32_t tm, tn;
-    tile_of_block((blk.z * atom.gy + blk.y) * atom.gx + blk.x, g.tiles_m, g.tiles_n, tm, tn);
+    tile_of_block(blk.y * atom.gx + blk.x, g.tiles_m, g.tiles_n, tm, tn);   // blk.z is the K slice
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -130,16 +133,21 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
     TileStage<SPLIT ? BM : T / 8, T, TA && SPLIT> sa2;   // lo plane of A (a dummy 32-row stage when unused)
     TileStage<BN, T, !TB> sb;       // B is k-strided in memory when NOT transposed
 
-    const int KT = (g.K + BK - 1) / BK;
-    sa.load(g.A, g.lda, m0, g.M, 0, g.K, tid);
-    if constexpr (SPLIT) sa2.load(g.A + g.a_plane, g.lda, m0, g.M, 0, g.K, tid);
-    sb.load(g.B, g.ldb, n0, g.N, 0, g.K, tid);
-    sa.store(As, tid);
-    if constexpr (SPLIT) sa2.store(As2, tid);
-    sb.store(Bs, tid);
+    int kt0, kt1;
+    slice_ktiles(g, blk.z, (g.K + BK - 1) / BK, kt0, kt1);
+    const int KT = kt1;
+    if (g.k_slices > 1) g.C = reinterpret_cast<float*>(g.C) + (int64_t)blk.z * g.c_slice;
+    if (kt0 < kt1) {
+        sa.load(g.A, g.lda, m0, g.M, kt0 * BK, g.K, tid);
+        if constexpr (SPLIT) sa2.load(g.A + g.a_plane, g.lda, m0, g.M, kt0 * BK, g.K, tid);
+        sb.load(g.B, g.ldb, n0, g.N, kt0 * BK, g.K, tid);
+        sa.store(As, tid);
+        if constexpr (SPLIT) sa2.store(As2, tid);
+        sb.store(Bs, tid);
+    }
     __syncthreads();
 
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int kt = kt0; kt < KT; ++kt) {
         if (kt + 1 < KT) {          // next tile's global loads fly during the MFMAs
             sa.load(g.A, g.lda, m0, g.M, (kt + 1) * BK, g.K, tid);
             if constexpr (SPLIT) sa2.load(g.A + g.a_plane, g.lda, m0, g.M, (kt + 1) * BK, g.K, tid);
@@ -185,7 +193,13 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
     if constexpr (ST) {
         // the operand buffers are free after the loop's last barrier
         constexpr int PPR = BN / 8;
-        if (m0 + BM <= g.M && n0 + BN <= g.N) {
+        if (m0 + BM <= g.M && n0 + BN <= g.N && (g.flags & LITHOS_F_OUT_F32)) {
+            static_for<MI * NI>([&](auto ij) {
+                constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
+                store_block_swapped_f32(g, reinterpret_cast<float*>(g.C), m0 + wm * WM + i * 32 + (lane & 31),
+                                        n0 + wn * WN + j * 32, acc[i][j], lane);
+            });
+        } else if (m0 + BM <= g.M && n0 + BN <= g.N) {
             uint16_t* const C = reinterpret_cast<uint16_t*>(g.C);
             static_for<MI * NI>([&](auto ij) {
                 constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;

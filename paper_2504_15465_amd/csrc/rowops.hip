@@ -20,7 +20,7 @@ struct RowArgs {
     int64_t rows, cols;
     float f0;            // eps / scale / theta
     uint32_t flags;
-    int64_t aux[4];
+    int64_t aux[5];
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
@@ -113,6 +113,56 @@ __global__ __launch_bounds__(256) void bias_act_kernel(RowArgs a, AtomArgs atom)
                 float hi = bf16_bits_to_f32(f32_to_bf16_bits(v));
                 reinterpret_cast<uint16_t*>(a.y)[total + idx] = f32_to_bf16_bits(v - hi);
             }
+        }
+    }
+}
+
+// ---- y = act(sum_z plane_z + bias) + residual: 2048 consecutive elements per block ----
+// The planes are the fp32 partial products of a K-sliced GEMM; they are added in
+// slice order, starting from plane 0, so the sum is the same for every launch shape.
+// VEC: four elements per thread and step (cols, strides and pointers permit 16-byte access).
+template <bool OUT32, bool VEC>
+__global__ __launch_bounds__(256) void sum_slices_kernel(RowArgs a, AtomArgs atom)
+{
+    const uint32_t L = atom_logical_block(atom);
+    const int64_t total = a.rows * a.cols;
+    const int64_t base = (int64_t)L * 2048;
+    const float* planes = reinterpret_cast<const float*>(a.x);
+    const int64_t S = a.aux[0], plane = a.aux[1], ldx = a.aux[2], ldy = a.aux[3];
+    const int64_t ldr = a.aux[4];
+    constexpr int W = VEC ? 4 : 1;
+#pragma unroll
+    for (int i = 0; i < 8 / W; ++i) {
+        const int64_t idx = base + ((int64_t)threadIdx.x + i * 256) * W;
+        if (idx >= total) continue;
+        const int64_t r = idx / a.cols, c = idx % a.cols;
+        float v[W];
+        if constexpr (VEC) {
+            float4 s = *reinterpret_cast<const float4*>(planes + r * ldx + c);
+            for (int64_t z = 1; z < S; ++z) {
+                const float4 t = *reinterpret_cast<const float4*>(planes + z * plane + r * ldx + c);
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+            v[0] = s.x; v[1] = s.y; v[2] = s.z; v[3] = s.w;
+        } else {
+            float s = planes[r * ldx + c];
+            for (int64_t z = 1; z < S; ++z) s += planes[z * plane + r * ldx + c];
+            v[0] = s;
+        }
+#pragma unroll
+        for (int t = 0; t < W; ++t) {
+            if (a.flags & LITHOS_F_BIAS) v[t] += a.p0[c + t];
+            if (a.flags & LITHOS_F_GELU) v[t] = gelu_erf_f(v[t]);
+            if (a.flags & LITHOS_F_RESIDUAL) v[t] += a.p1[r * ldr + c + t];
+        }
+        if constexpr (VEC && OUT32) {
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + r * ldy + c) = make_float4(v[0], v[1], v[2], v[3]);
+        } else if constexpr (VEC) {
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.y) + r * ldy + c) =
+                make_uint2(f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16),
+                           f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16));
+        } else {
+            store_elem<OUT32>(a.y, r * ldy + c, v[0]);
         }
     }
 }
@@ -431,6 +481,21 @@ int rowops_plan(const lithos_op_t& op, OpPlan* plan)
         if (!op.out[0]) return fail(LITHOS_EINVAL, "silu_mul: null output");
         blocks = ((uint64_t)rows * cols + 2047) / 2048;
         break;
+    case LITHOS_OP_SUM_SLICES: {
+        // dim = rows, cols, slices, slice plane stride; ld = row strides of the planes, of y, of the residual
+        const int64_t S = op.dim[2], plane = op.dim[3], ldx = op.ld[0], ldy = op.ld[1], ldr = op.ld[2];
+        if (!op.out[0]) return fail(LITHOS_EINVAL, "sum_slices: null output");
+        if (S < 1 || S > LITHOS_GEMM_MAX_SLICES) return fail(LITHOS_EINVAL, "sum_slices: slices must be in [1, %d]", LITHOS_GEMM_MAX_SLICES);
+        if (ldx < cols || ldy < cols || plane < rows * ldx) return fail(LITHOS_EINVAL, "sum_slices: row or plane stride too small");
+        if ((op.flags & LITHOS_F_BIAS) && !op.in[1]) return fail(LITHOS_EINVAL, "sum_slices: BIAS set but in[1] is null");
+        if ((op.flags & LITHOS_F_RESIDUAL) && (!op.in[2] || ldr < cols)) return fail(LITHOS_EINVAL, "sum_slices: RESIDUAL needs in[2] and ld[2] >= cols");
+        if (op.flags & (LITHOS_F_IN_F32 | LITHOS_F_OUT_SPLIT)) return fail(LITHOS_EINVAL, "sum_slices: the planes are always fp32; no split output");
+        blocks = ((uint64_t)rows * cols + 2047) / 2048;
+        if (cols % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && plane % 4 == 0 && aligned16(op.in[0]) && aligned16(op.out[0]) &&
+            (!(op.flags & LITHOS_F_RESIDUAL) || ldr % 4 == 0))
+            plan->variant = 1;
+        break;
+    }
     case LITHOS_OP_LAYERNORM:
         if (!op.in[1] || !op.in[2] || !op.out[0]) return fail(LITHOS_EINVAL, "layernorm: null gamma, beta or output");
         if (!(op.flags & LITHOS_F_OUT_F32) && op.out[1]) return fail(LITHOS_EINVAL, "layernorm: a bf16 copy needs OUT_F32");
@@ -489,6 +554,12 @@ int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& ato
     case LITHOS_OP_SILU_MUL:
         if (in32) { if (out32) L2(silu_mul_kernel, true, true); else L2(silu_mul_kernel, true, false); }
         else      { if (out32) L2(silu_mul_kernel, false, true); else L2(silu_mul_kernel, false, false); }
+        break;
+    case LITHOS_OP_SUM_SLICES:
+        a.aux[0] = op.dim[2]; a.aux[1] = op.dim[3]; a.aux[2] = op.ld[0]; a.aux[3] = op.ld[1];
+        a.aux[4] = op.ld[2];
+        if (plan.variant == 1) { if (out32) L2(sum_slices_kernel, true, true); else L2(sum_slices_kernel, false, true); }
+        else                   { if (out32) L2(sum_slices_kernel, true, false); else L2(sum_slices_kernel, false, false); }
         break;
     case LITHOS_OP_LAYERNORM:
         if (plan.variant == 1) {          // register-resident rows

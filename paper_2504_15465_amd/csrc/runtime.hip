@@ -63,6 +63,7 @@ int op_plan(const lithos_op_t& op, OpPlan* plan)
     case LITHOS_OP_RMSNORM:
     case LITHOS_OP_ROPE_KV:
     case LITHOS_OP_SILU_MUL:
+    case LITHOS_OP_SUM_SLICES:
     case LITHOS_OP_SPIN: return rowops_plan(op, plan);
     default: return fail(LITHOS_EINVAL, "unknown operator kind %d", op.kind);
     }
@@ -382,6 +383,25 @@ int lithos_op_grid(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3* grid_o
     if (rc != LITHOS_OK) return rc;
     if (grid_out) *grid_out = plan.grid;
     if (wg_per_cu_out) *wg_per_cu_out = plan.wg_per_cu;
+    return LITHOS_OK;
+}
+
+int lithos_gemm_split_hint(const lithos_op_t* op, int32_t n_cus, int32_t* tile_out, int32_t* slices_out)
+{
+    if (!op || !tile_out || !slices_out || op->kind != LITHOS_OP_GEMM || n_cus <= 0)
+        return fail(LITHOS_EINVAL, "lithos_gemm_split_hint: need a GEMM descriptor, a CU count and both outputs");
+    const int64_t M = op->dim[0], N = op->dim[1], K = op->dim[2];
+    if (M <= 0 || N <= 0 || K <= 0) return fail(LITHOS_EINVAL, "lithos_gemm_split_hint: M,N,K must be positive");
+    *tile_out = 0;
+    *slices_out = 1;
+    // 256x256 tiles run one workgroup per CU.  With fewer than 3/4 of the CUs covered, cut K so
+    // that tiles * slices just fits the CUs, keeping at least 8 k-tiles (512 of K) per slice.
+    const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256), kt = (K + 63) / 64;
+    if (M < 128 || N < 128 || tiles * 4 >= (int64_t)n_cus * 3) return LITHOS_OK;
+    int64_t s = n_cus / tiles;
+    if (s > kt / 8) s = kt / 8;
+    if (s > LITHOS_GEMM_MAX_SLICES) s = LITHOS_GEMM_MAX_SLICES;
+    if (s >= 2) { *tile_out = LITHOS_TILE_256; *slices_out = (int32_t)s; }
     return LITHOS_OK;
 }
 

@@ -13,6 +13,21 @@ from paper_2504_15465_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def test_gemm_split_hint_fills_the_partition():
+    """Host-only entry point: output tiles x K slices is about one workgroup per CU."""
+    def hint(m, n, k, cus):
+        return B.lithos_gemm_split_hint(B.make_op(B.OP_GEMM, (m, n, k)), cus)
+    assert hint(1024, 3072, 16384, 256) == (256, 5)       # 48 tiles x 5 = 240 workgroups
+    assert hint(1024, 1024, 16384, 256) == (256, 16)
+    assert hint(1024, 4096, 16384, 192) == (256, 3)
+    assert hint(8192, 8192, 8192, 256) == (0, 1)          # 1024 tiles fill the chip: leave it whole
+    assert hint(1024, 1024, 1024, 256) == (256, 2)        # at least 8 k-tiles per slice
+    assert hint(1024, 1024, 512, 256) == (0, 1)           # K too short to cut
+    assert hint(8, 4096, 4096, 64) == (0, 1)              # weight-streaming shapes are not cut
+    with pytest.raises(B.LithosError):
+        B.lithos_gemm_split_hint(B.make_op(B.OP_SPIN, (4, 10)), 64)
+
+
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "lithos.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)

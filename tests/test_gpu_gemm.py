@@ -232,3 +232,101 @@ def test_split_bf16_activations_and_outputs(tile, tb):
     assert np.abs(got - ref).max() <= 2.0 ** -15 * np.abs(ref).max() + 1e-6
     with pytest.raises(B.LithosError):
         B.lithos_launch_atomized(ctx(), B.gemm_op(a_pair, b, c, m, n, k, tb=tb, tile=256, a_split=True))
+
+
+@pytest.mark.parametrize("tile,ta,tb,m,n,k,slices", [
+    (64, True, False, 200, 136, 1000, 7),       # dW-shaped: both operands k-strided, ragged everywhere
+    (128, False, False, 392, 264, 520, 3),
+    (128, True, True, 256, 128, 512, 8),        # one k-tile per slice
+    (256, False, True, 520, 776, 640, 4),       # k-contiguous operands, K % 64 == 0: the direct-to-LDS kernel
+    (256, False, True, 256, 512, 320, 2),       # odd number of k-tiles, uneven cut (2 + 3)
+    (256, True, False, 512, 264, 2048, 5),
+])
+def test_k_sliced_gemm_and_sum_of_slices(tile, ta, tb, m, n, k, slices):
+    """K cut into ranges on the logical grid's z axis: every plane equals the oracle's product over
+    its K range, the planes' ordered sum equals the whole product, any atom size gives the same bits
+    and runs every (tile, slice) block once; SUM_SLICES with the fused epilogue against the oracle."""
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=31 + slices, ta=ta, tb=tb)
+    a, b = dev_bits(a_bits), dev_bits(b_bits)
+
+    def planes_with(atom_blocks, count=False):
+        ws = nan_like((slices, m, n), torch.float32)
+        op = B.gemm_op(a, b, ws, m, n, k, ta=ta, tb=tb, tile=tile, k_slices=slices)
+        grid, _ = B.lithos_op_grid(ctx(), op)
+        cnt = counters(grid[0] * grid[1] * grid[2]) if count else None
+        if count:
+            B.lithos_debug_block_counters(ctx(), cnt)
+        torch.cuda.synchronize()
+        try:
+            B.lithos_launch_atomized(ctx(), op, (0, 0, 0), atom_blocks, None, None)
+            B.lithos_partition_sync(ctx(), None)
+        finally:
+            B.lithos_debug_block_counters(ctx(), None)
+        return ws, grid, cnt
+
+    ws, grid, _ = planes_with(0)
+    assert grid[2] == slices and not torch.isnan(ws).any()
+    bounds = O.k_slice_bounds(k, slices)
+    ref_planes = []
+    for z, (lo, hi) in enumerate(bounds):
+        az = a_bits[lo:hi] if ta else a_bits[:, lo:hi]
+        bz = b_bits[:, lo:hi] if tb else b_bits[lo:hi]
+        ref_planes.append(O.gemm(az, bz, ta=ta, tb=tb))
+        assert rel_fro(ws[z], ref_planes[z]) <= FRO_TOL
+    total = grid[0] * grid[1] * grid[2]
+    for atom_blocks in (1, 5, total - 1):
+        ws_atom, _, cnt = planes_with(atom_blocks, count=True)
+        assert cnt.cpu().tolist() == [1] * total
+        assert bits_equal(ws_atom, ws)
+
+    ref = O.gemm(a_bits, b_bits, ta=ta, tb=tb)
+    def summed(out_dtype, atom_blocks=0, **epi):
+        y = nan_like((m, n), out_dtype)
+        op = B.sum_slices_op(ws, y, m, n, slices, **epi)
+        torch.cuda.synchronize()
+        B.lithos_launch_atomized(ctx(), op, (0, 0, 0), atom_blocks, None, None)
+        B.lithos_partition_sync(ctx(), None)
+        return y
+    y32 = summed(torch.float32)
+    assert rel_fro(y32, ref) <= FRO_TOL
+    assert bits_equal(summed(torch.float32, atom_blocks=3), y32)
+    # the ordered fp32 sum of the GPU's own planes, formed on the host in the same order
+    host = ws[0].cpu().numpy().copy()
+    for z in range(1, slices):
+        host = (host + ws[z].cpu().numpy()).astype(np.float32)
+    assert np.array_equal(host, y32.cpu().numpy())
+    bias = inputs.normal_f32((n,), 10, 0.5)
+    resid = inputs.normal_f32((m, n), 11, 1.0)
+    ref_epi = O.bias_act(O.sum_slices(np.stack(ref_planes)), bias.astype(np.float64), gelu=True) + resid.astype(np.float64)
+    y16 = summed(torch.bfloat16, bias=torch.from_numpy(bias).cuda(), gelu=True, residual=torch.from_numpy(resid).cuda())
+    bf16_close(y16, ref_epi, abs_tol=2.0 ** -22 * k)
+    y16a = summed(torch.bfloat16, atom_blocks=2, bias=torch.from_numpy(bias).cuda(), gelu=True, residual=torch.from_numpy(resid).cuda())
+    assert bits_equal(y16, y16a)
+
+
+def test_sum_slices_unaligned_shapes_take_the_scalar_path():
+    rows, cols, s = 37, 101, 3
+    planes = inputs.normal_f32((s, rows, cols), 3, 1.0)
+    y = nan_like((rows, cols), torch.float32)
+    op = B.sum_slices_op(torch.from_numpy(planes).cuda(), y, rows, cols, s)
+    torch.cuda.synchronize()
+    B.lithos_launch_atomized(ctx(), op, (0, 0, 0), 0, None, None)
+    B.lithos_partition_sync(ctx(), None)
+    want = ((planes[0] + planes[1]).astype(np.float32) + planes[2]).astype(np.float32)
+    assert np.array_equal(y.cpu().numpy(), want)
+    assert np.abs(y.cpu().numpy().astype(np.float64) - O.sum_slices(planes.astype(np.float64))).max() <= 1e-6
+
+
+def test_k_slices_bad_arguments():
+    a = torch.zeros((64, 256), dtype=torch.bfloat16, device="cuda")
+    c16 = torch.zeros((4, 64, 64), dtype=torch.bfloat16, device="cuda")
+    c32 = torch.zeros((4, 64, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.LithosError):      # partial planes are fp32
+        B.lithos_op_grid(ctx(), B.gemm_op(a, a, c16, 64, 64, 256, tb=True, tile=64, k_slices=4))
+    with pytest.raises(B.LithosError):      # more slices than k-tiles
+        B.lithos_op_grid(ctx(), B.gemm_op(a, a, c32, 64, 64, 256, tb=True, tile=64, k_slices=5))
+    with pytest.raises(B.LithosError):      # plane stride too small
+        B.lithos_op_grid(ctx(), B.gemm_op(a, a, c32, 64, 64, 256, tb=True, tile=64, k_slices=4, slice_plane=64 * 63))
+    with pytest.raises(B.LithosError):      # the epilogue belongs to SUM_SLICES
+        B.lithos_op_grid(ctx(), B.gemm_op(a, a, c32, 64, 64, 256, tb=True, tile=64, k_slices=4, gelu=True))
+    assert B.lithos_op_grid(ctx(), B.gemm_op(a, a, c32, 64, 64, 256, tb=True, tile=64, k_slices=4))[0] == (1, 1, 4)

@@ -111,6 +111,32 @@ def test_gemm_matches_blas_fp64_and_transposes():
                     ops.gemm(a_bits, b_bits, ta=not ta, tb=tb)
 
 
+def test_sum_slices_closed_forms_and_k_cut_of_a_gemm():
+    # planes of constants: 1 + 2 + ... + S
+    for s in (1, 2, 5):
+        planes = np.stack([np.full((3, 4), z + 1.0) for z in range(s)])
+        assert np.all(ops.sum_slices(planes) == s * (s + 1) / 2)
+    one = np.arange(12.0).reshape(1, 3, 4)
+    assert np.array_equal(ops.sum_slices(one), one[0])
+    # the cut covers K exactly once, in order, in whole 64-wide steps (the last range may be ragged)
+    for k, s in ((200, 3), (64, 1), (1000, 7), (16384, 5)):
+        b = ops.k_slice_bounds(k, s)
+        assert b[0][0] == 0 and b[-1][1] == k and all(x[1] == y[0] for x, y in zip(b, b[1:]))
+        assert all(lo % 64 == 0 and lo <= hi for lo, hi in b)
+        assert max(hi - lo for lo, hi in b) - min(hi - lo for lo, hi in b) <= 64 + (-k) % 64
+    # a GEMM on exactly representable data equals the sum of its K ranges bit for bit
+    rng = np.random.default_rng(3)
+    a = rng.choice([-2.0, -1.0, -0.5, 0.5, 1.0, 2.0], size=(9, 200))
+    bm = rng.choice([-2.0, -1.0, -0.5, 0.5, 1.0, 2.0], size=(200, 7))
+    a_bits, b_bits = inputs.to_bf16_bits(a), inputs.to_bf16_bits(bm)
+    parts = np.stack([ops.gemm(a_bits[:, lo:hi], b_bits[lo:hi]) for lo, hi in ops.k_slice_bounds(200, 3)])
+    assert np.array_equal(ops.sum_slices(parts), ops.gemm(a_bits, b_bits))
+    # and on random data up to fp64 rounding of the regrouped sum
+    a_bits, b_bits = inputs.gemm_operands(9, 7, 200, seed=5)
+    parts = np.stack([ops.gemm(a_bits[:, lo:hi], b_bits[lo:hi]) for lo, hi in ops.k_slice_bounds(200, 3)])
+    np.testing.assert_allclose(ops.sum_slices(parts), ops.gemm(a_bits, b_bits), rtol=0, atol=1e-12)
+
+
 def test_gemm_frobenius_scale_of_uniform_inputs():
     # entries U[-1,1] have variance 1/3, so C elements have std sqrt(K)/3
     a_bits, b_bits = inputs.gemm_operands(128, 128, 512, seed=0)
