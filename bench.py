@@ -55,13 +55,13 @@ def nearest_rank(x, q):
 
 def be_gemm_8192(B, inputs, torch, tile):
     n = 8192
-    # y = x W^T with the weights stored [N,K], the layout of a linear layer's forward pass
-    a_bits, b_bits = inputs.gemm_operands(n, n, n, seed=4, tb=True)
+    # C = A B, both row-major
+    a_bits, b_bits = inputs.gemm_operands(n, n, n, seed=4)
     a, b = inputs.bits_to_torch(a_bits, "cuda").contiguous(), inputs.bits_to_torch(b_bits, "cuda").contiguous()
     c = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
-    op = B.gemm_op(a, b, c, n, n, n, tile=tile, tb=True)
-    desc = ("gemm_nt256_kernel" if tile == 256 else "gemm_tile_kernel<%d,%d>" % (tile, tile)) + \
-        " 8192^3 bf16 (A [M,K], B [N,K]), whole launch, 256 CUs"
+    op = B.gemm_op(a, b, c, n, n, n, tile=tile)
+    desc = ("gemm_lds256_kernel" if tile == 256 else "gemm_tile_kernel<%d,%d>" % (tile, tile)) + \
+        " 8192^3 bf16 (A [M,K], B [K,N]), whole launch, 256 CUs"
     return dict(ops=[op], flop=2.0 * n ** 3, dominant=(op, 2.0 * n ** 3, desc), host=(a_bits, b_bits),
                 text="bf16 8192^3 GEMMs back to back")
 
@@ -82,7 +82,7 @@ def wl_cfg2(args, B, inputs, torch):
         hp_ms = (time.perf_counter() - t0) * 1e3
         rows = 32
         t0 = time.perf_counter()
-        O.gemm(be["host"][0][:rows], be["host"][1], tb=True)
+        O.gemm(be["host"][0][:rows], be["host"][1])
         be_s = time.perf_counter() - t0
         return {"value": hp_ms, "unit": "ms", "cores": O.num_threads(), "kind": "oracle",
                 "sample": "1 high-priority request (6 layers, batch 8) = value (no queueing, no tenants); plus %d of "
@@ -140,7 +140,7 @@ def wl_cfg3(args, B, inputs, torch):
     chain.set_input(x)
     ops, flop, keep, distinct = training_block_ops(B, inputs, torch)
     dom = distinct["be_ffn1_fwd"]
-    be = dict(ops=ops, flop=flop, dominant=(dom[0], dom[1], "gemm_tile_kernel 16384x4096x1024 bf16 (FFN1 forward), whole launch, 256 CUs"),
+    be = dict(ops=ops, flop=flop, dominant=(dom[0], dom[1], "gemm_lds256_kernel 16384x4096x1024 bf16 (FFN1 forward), whole launch, 256 CUs"),
               text="fwd + dX + dW GEMMs of a 24-layer hidden-1024 FFN-4096 block over 16384 tokens (288 GEMMs per iteration)")
 
     def cpu_baseline():

@@ -34,7 +34,7 @@ static bool staged_epilogue(const lithos_op_t& op)
 static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split, bool st)
 {
     switch (variant) {
-    case V_NT256: return gemm_nt256_fn(st);
+    case V_LDS256: return gemm_lds256_fn(ta, tb, st);
     case V_TILE64: return gemm_tile64_fn(ta, tb, split, st);
     case V_TILE128: return gemm_tile128_fn(ta, tb, split, st);
     case V_TILE256: return gemm_tile256_fn(ta, tb, st);
@@ -96,7 +96,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
     } else if (tile == 64 || tile == 128 || tile == 256) {
         if (split && tile == 256) return fail(LITHOS_EINVAL, "gemm: SPLIT_A is built for the 64 and 128 tiles only");
         variant = tile == 64 ? V_TILE64 : tile == 128 ? V_TILE128 : V_TILE256;
-        if (tile == 256 && !ta && tb && K % 64 == 0) variant = V_NT256;
+        if (tile == 256 && K % 64 == 0) variant = V_LDS256;
         plan->grid = {(uint32_t)((N + tile - 1) / tile), (uint32_t)((M + tile - 1) / tile), (uint32_t)(slices > 1 ? slices : 1)};
     } else {
         return fail(LITHOS_EINVAL, "gemm: unknown tile selector %d", tile);

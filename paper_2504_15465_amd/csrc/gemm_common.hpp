@@ -187,13 +187,13 @@ typedef void (*gemm_fn)(GemmArgs, AtomArgs);
 gemm_fn gemm_tile64_fn(bool ta, bool tb, bool split, bool st);
 gemm_fn gemm_tile128_fn(bool ta, bool tb, bool split, bool st);
 gemm_fn gemm_tile256_fn(bool ta, bool tb, bool st);
-gemm_fn gemm_nt256_fn(bool st);
+gemm_fn gemm_lds256_fn(bool ta, bool tb, bool st);
 gemm_fn gemm_skinny_fn(int variant, bool a32);
 
 constexpr int SKINNY_WAVES = 8;     // wavefronts per workgroup of the skinny kernels, each owning one slice of K
 constexpr int SKINNY_NB = 2;        // 16-column blocks per workgroup of the skinny kernels
 
-enum { V_SKINNY32 = 3, V_TILE64 = 10, V_TILE128 = 20, V_TILE256 = 30, V_NT256 = 31,
+enum { V_SKINNY32 = 3, V_TILE64 = 10, V_TILE128 = 20, V_TILE256 = 30, V_LDS256 = 31,
        V_SKL4 = 40, V_SKL8 = 41, V_SKL16 = 42 };   // LDS-staged activations of at most 4 / 8 / 16 rows
 
 } // namespace lithos

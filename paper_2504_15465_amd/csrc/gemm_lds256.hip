@@ -2,19 +2,33 @@
 
 namespace lithos {
 
-// ---- 256x256 tile, both operands k-contiguous, global -> LDS without registers ---
-// C = A B^T with A [M,K] and B [N,K] (TRANS_B), K a multiple of 64.  The k-tiles go
-// from global memory straight into LDS (global_load_lds_dwordx4: the 64 lanes of a
-// wavefront fill 1 KB of LDS in lane order, so each lane fetches the 16-byte chunk
-// that the swizzled layout wants at its position).  That frees the 32 staging
+// ---- 256x256 tile, K a multiple of 64, global -> LDS without registers -------------
+// The k-tiles go from global memory straight into LDS (global_load_lds_dwordx4: the 64
+// lanes of a wavefront fill 1 KB of LDS in lane order, so each lane fetches the 16-byte
+// chunk that the swizzled layout wants at its position).  That frees the 32 staging
 // registers of the general kernel, which pay for a second set of operand fragments:
 // the LDS reads of step kk+1 are issued before the MFMAs of step kk.
+//
+// An operand that is k-contiguous in memory (A [M,K]; B given as [N,K]) lies in LDS as
+// [row][64 k] and a lane reads its 8 consecutive k with one 16-byte load.  An operand that
+// is k-strided in memory (KSA: A given as [K,M]; KSB: B given as [K,N]) lies in LDS as it
+// lies in memory, [64 k][256 rows], and is read with the transposing LDS load
+// (ds_read_b64_tr_b16): within 16 lanes, source lane s supplies 4 consecutive rows of
+// k-row s/4, and lane l receives row l of the four k-rows: 4 consecutive k of one row,
+// which is the MFMA operand layout.  Two such loads make a fragment; nothing is
+// transposed in registers.
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-template <int WGM, int WGN, bool ST>
+// [64 k][256 rows] tile: 16-byte chunk c of k-row k is stored at chunk c ^ ((k & 3) << 2), so
+// the four k-rows that one transposing load touches fall into different banks.
+__device__ __forceinline__ int ks_index(int k, int row) { return k * 256 + ((((row >> 3) ^ ((k & 3) << 2))) << 3) + (row & 7); }
+
+template <int WGM, int WGN, bool ST, bool KSA, bool KSB>
 __global__ __launch_bounds__(WGM * WGN * 64)
-void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
+void gemm_lds256_kernel(GemmArgs g, AtomArgs atom)
 {
     static_assert(!ST || (WGM == 2 && WGN == 4), "the staged epilogue maps 32-row blocks to the four 64-row buffers");
     constexpr int BM = 256, BN = 256, BK = 64, WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
@@ -43,25 +57,36 @@ void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // Wavefront w fills LDS blocks 4w..4w+3 of each operand; a block is 8 rows x 8 chunks
-    // of 16 bytes, and lane l lands on row l/8, stored chunk l%8, which holds the logical
-    // chunk (l%8) ^ swizzle(row).  Rows beyond the matrix re-read its last row.
+    // Wavefront w fills LDS blocks 4w..4w+3 of each operand.  k-contiguous operand: a block is
+    // 8 rows x 8 chunks of 16 bytes, and lane l lands on row l/8, stored chunk l%8, which holds
+    // the logical chunk (l%8) ^ swizzle(row); rows beyond the matrix re-read its last row.
+    // k-strided operand: a block is 2 k-rows x 32 chunks, lane l lands on k-row l/32, stored
+    // chunk l%32; chunks beyond the matrix re-read the row's last chunk.
+    auto lane_ptr = [&](auto ks, const uint16_t* base, int64_t ld, int r0, int rows, int blkno) {
+        if constexpr (decltype(ks)::value) {
+            const int k = blkno * 2 + (lane >> 5);
+            const int c = (lane & 31) ^ ((k & 3) << 2);
+            return base + (int64_t)k * ld + min(r0 + c * 8, rows - 8);
+        } else {
+            const int row = blkno * 8 + (lane >> 3);
+            const int kc = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
+            return base + (int64_t)min(r0 + row, rows - 1) * ld + kc * 8;
+        }
+    };
     const uint16_t* ga[NBLK];
     const uint16_t* gb[NBLK];
 #pragma unroll
     for (int i = 0; i < NBLK; ++i) {
-        const int row = (wave * NBLK + i) * 8 + (lane >> 3);
-        const int kc = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
-        ga[i] = g.A + (int64_t)min(m0 + row, g.M - 1) * g.lda + kc * 8;
-        gb[i] = g.B + (int64_t)min(n0 + row, g.N - 1) * g.ldb + kc * 8;
+        ga[i] = lane_ptr(std::bool_constant<KSA>{}, g.A, g.lda, m0, g.M, wave * NBLK + i);
+        gb[i] = lane_ptr(std::bool_constant<KSB>{}, g.B, g.ldb, n0, g.N, wave * NBLK + i);
     }
-    auto fetch1 = [&](uint16_t* Ad, uint16_t* Bd, int k0, int i) {
-        __builtin_amdgcn_global_load_lds((gptr_t)(ga[i] + k0), (lptr_t)(Ad + (wave * NBLK + i) * 512), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + k0), (lptr_t)(Bd + (wave * NBLK + i) * 512), 16, 0, 0);
-    };
+    const int64_t a_kstep = KSA ? g.lda : 1, b_kstep = KSB ? g.ldb : 1;    // elements per unit of k
     auto fetch = [&](uint16_t* Ad, uint16_t* Bd, int k0) {
 #pragma unroll
-        for (int i = 0; i < NBLK; ++i) fetch1(Ad, Bd, k0, i);
+        for (int i = 0; i < NBLK; ++i) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(ga[i] + k0 * a_kstep), (lptr_t)(Ad + (wave * NBLK + i) * 512), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(gb[i] + k0 * b_kstep), (lptr_t)(Bd + (wave * NBLK + i) * 512), 16, 0, 0);
+        }
     };
 
     int kt0, KT;                                    // this block's k-tiles are [kt0, KT)
@@ -69,14 +94,25 @@ void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
     if (g.k_slices > 1) g.C = reinterpret_cast<float*>(g.C) + (int64_t)blk.z * g.c_slice;
     // Operand fragments: set 0 and set 1 alternate between the four 16-wide k-steps of a tile.
     bf16x8 af[2][MI], bfr[2][NI];
+    // one 32-row fragment of k-step kk: rows r0 .. r0+31 of the tile, this lane's 8 k
+    auto read_frag = [&](auto ks, const uint16_t* T, int r0, int kk) -> bf16x8 {
+        if constexpr (decltype(ks)::value) {
+            // source lane s of a 16-lane group addresses k-row s/4, rows 4*(s%4)..+3 of the group's 16
+            const int grp = lane >> 4, s = lane & 15;
+            const int k = kk * 16 + 8 * (grp >> 1) + (s >> 2);
+            const int row = r0 + 16 * (grp & 1) + 4 * (s & 3);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(T + ks_index(k, row)));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(T + ks_index(k + 4, row)));
+            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        } else {
+            return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(T + lds_index(r0 + (lane & 31), kk * 2 + (lane >> 5))));
+        }
+    };
     auto read_frags = [&](const uint16_t* Ac, const uint16_t* Bc, int kk, bf16x8 (&a)[MI], bf16x8 (&b)[NI]) {
-        const int kc = kk * 2 + (lane >> 5);
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
-            a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Ac + lds_index(wm * WM + i * 32 + (lane & 31), kc)));
+        for (int i = 0; i < MI; ++i) a[i] = read_frag(std::bool_constant<KSA>{}, Ac, wm * WM + i * 32, kk);
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
-            b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Bc + lds_index(wn * WN + j * 32 + (lane & 31), kc)));
+        for (int j = 0; j < NI; ++j) b[j] = read_frag(std::bool_constant<KSB>{}, Bc, wn * WN + j * 32, kk);
     };
     // the MFMAs of one step; the LDS reads of the next step are issued after the first NI of
     // them, so that the wait in front of a step only covers reads that are a step old
@@ -179,9 +215,13 @@ void gemm_nt256_kernel(GemmArgs g, AtomArgs atom)
     });
 }
 
-gemm_fn gemm_nt256_fn(bool st)
+gemm_fn gemm_lds256_fn(bool ta, bool tb, bool st)
 {
-    return st ? (gemm_fn)gemm_nt256_kernel<2, 4, true> : (gemm_fn)gemm_nt256_kernel<2, 4, false>;
+#define PICK(ST)                                                                                       \
+    (ta ? (tb ? (gemm_fn)gemm_lds256_kernel<2, 4, ST, true, false> : (gemm_fn)gemm_lds256_kernel<2, 4, ST, true, true>)    \
+        : (tb ? (gemm_fn)gemm_lds256_kernel<2, 4, ST, false, false> : (gemm_fn)gemm_lds256_kernel<2, 4, ST, false, true>))
+    return st ? PICK(true) : PICK(false);
+#undef PICK
 }
 
 } // namespace lithos

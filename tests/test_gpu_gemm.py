@@ -86,6 +86,25 @@ def test_nt_256_tile_with_k_multiple_of_64(m, n, k):
         assert bits_equal(c_atom, c_full)
 
 
+@pytest.mark.parametrize("ta,tb", [(False, False), (True, False), (True, True)])
+@pytest.mark.parametrize("m,n,k", [(520, 776, 320), (256, 256, 64), (304, 264, 128), (8, 8, 192)])
+def test_256_tile_k_strided_operands_read_through_transposing_lds_loads(ta, tb, m, n, k):
+    """256x256 tiles with K % 64 == 0 and an operand stored [K,rows]: the tile lies in LDS as in
+    memory and the fragments come from the transposing LDS load; ragged M and N, bf16 and fp32 C."""
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=78 + 2 * ta + tb, ta=ta, tb=tb)
+    ref = O.gemm(a_bits, b_bits, ta=ta, tb=tb)
+    c_full, grid, _ = run_gemm(a_bits, b_bits, m, n, k, ta, tb, 256)
+    assert not torch.isnan(c_full).any()
+    assert rel_fro(c_full, ref) <= FRO_TOL
+    total = grid[0] * grid[1]
+    for atom_blocks in sorted({1, max(1, total - 1)}):
+        c_atom, _, cnt = run_gemm(a_bits, b_bits, m, n, k, ta, tb, 256, atom_blocks=atom_blocks, count=True)
+        assert cnt.cpu().tolist() == [1] * total
+        assert bits_equal(c_atom, c_full)
+    c16, _, _ = run_gemm(a_bits, b_bits, m, n, k, ta, tb, 256, out_dtype=torch.bfloat16)
+    bf16_close(c16, ref, abs_tol=2.0 ** -22 * k)
+
+
 def test_exactly_representable_data_matches_oracle_bit_for_bit():
     rng = np.random.default_rng(1)
     vals = np.array([1, -1, .5, -.5, 2, -2], np.float32)
