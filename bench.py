@@ -94,43 +94,6 @@ def wl_cfg2(args, B, inputs, torch):
                 hp_requests=[chain.ops(x) for x in pool], rate=200.0, be=be, cpu_baseline=cpu_baseline, keep=[chain, pool])
 
 
-def training_block_ops(B, inputs, torch, n_layers=24, hidden=1024, ffn=4096, tokens=16384, split_cus=192):
-    """Forward and backward GEMMs (Y = XW, dX = dY W^T, dW = X^T dY) of a transformer block stack."""
-    dev, bf = "cuda", torch.bfloat16
-    shapes = [("qkv", hidden, 3 * hidden), ("out", hidden, hidden), ("ffn1", hidden, ffn), ("ffn2", ffn, hidden)]
-    x = {k: inputs.bits_to_torch(inputs.normal_bits((tokens, k), [12, k]), dev) for k in {s[1] for s in shapes}}
-    dy = {n: inputs.bits_to_torch(inputs.normal_bits((tokens, n), [13, n]), dev) for n in {s[2] for s in shapes}}
-    y = {n: torch.empty((tokens, n), dtype=bf, device=dev) for n in {s[2] for s in shapes}}
-    dx = {k: torch.empty((tokens, k), dtype=bf, device=dev) for k in {s[1] for s in shapes}}
-    ops, flop, keep, distinct = [], 0.0, [x, dy, y, dx], {}
-    planes = None       # fp32 partial planes of the K-sliced weight gradients (one buffer: the queue is in order)
-    for layer in range(n_layers):
-        for name, k, n in shapes:
-            w = inputs.bits_to_torch(inputs.normal_bits((k, n), [14, layer, k, n], 0.02), dev)
-            dw = torch.empty((k, n), dtype=bf, device=dev)
-            keep += [w, dw]
-            trio = [B.gemm_op(x[k], w, y[n], tokens, n, k),                       # Y  = X W
-                    B.gemm_op(dy[n], w, dx[k], tokens, k, n, tb=True),            # dX = dY W^T
-                    B.gemm_op(x[k], dy[n], dw, k, n, tokens, ta=True)]            # dW = X^T dY
-            # few output tiles, K = tokens: cut K so that every CU of the partition gets a tile
-            tile, slices = B.lithos_gemm_split_hint(trio[2], split_cus)
-            extra = []
-            if slices > 1:
-                if planes is None or planes.numel() < slices * k * n:     # grows during the first layer only
-                    planes = torch.empty(slices * k * n, dtype=torch.float32, device=dev)
-                    keep.append(planes)
-                trio[2] = B.gemm_op(x[k], dy[n], planes, k, n, tokens, ta=True, tile=tile, k_slices=slices)
-                extra = [B.sum_slices_op(planes, dw, k, n, slices)]
-            ops += trio + extra
-            flop += 3 * 2.0 * tokens * k * n
-            if layer == 0:
-                for kind, o in zip(("fwd", "dX", "dW"), trio):
-                    distinct["be_%s_%s" % (name, kind)] = (o, 2.0 * tokens * k * n)
-                if extra:
-                    distinct["be_%s_dW_sum" % name] = (extra[0], 0.0)
-    return ops, flop, keep, distinct
-
-
 def wl_cfg3(args, B, inputs, torch):
     from paper_2504_15465_amd.models import EncoderChain
     b = args.batch
@@ -138,7 +101,8 @@ def wl_cfg3(args, B, inputs, torch):
     chain = EncoderChain(layers, b, 128, 12)
     x = inputs.encoder_hidden(b, 128, 768, seed=11)
     chain.set_input(x)
-    ops, flop, keep, distinct = training_block_ops(B, inputs, torch)
+    from paper_2504_15465_amd.models import training_block_ops
+    ops, flop, keep, distinct = training_block_ops()
     dom = distinct["be_ffn1_fwd"]
     be = dict(ops=ops, flop=flop, dominant=(dom[0], dom[1], "gemm_lds256_kernel 16384x4096x1024 bf16 (FFN1 forward), whole launch, 256 CUs"),
               text="fwd + dX + dW GEMMs of a 24-layer hidden-1024 FFN-4096 block over 16384 tokens (288 GEMMs per iteration)")

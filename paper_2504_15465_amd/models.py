@@ -218,3 +218,41 @@ class DecoderChain:
 
     def set_input(self, x32: np.ndarray):
         self.x_in.copy_(torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)))
+
+
+def training_block_ops(n_layers=24, hidden=1024, ffn=4096, tokens=16384, split_cus=192):
+    """Forward and backward GEMMs (Y = XW, dX = dY W^T, dW = X^T dY) of a transformer block stack."""
+    dev, bf = "cuda", torch.bfloat16
+    from . import inputs
+    shapes = [("qkv", hidden, 3 * hidden), ("out", hidden, hidden), ("ffn1", hidden, ffn), ("ffn2", ffn, hidden)]
+    x = {k: inputs.bits_to_torch(inputs.normal_bits((tokens, k), [12, k]), dev) for k in {s[1] for s in shapes}}
+    dy = {n: inputs.bits_to_torch(inputs.normal_bits((tokens, n), [13, n]), dev) for n in {s[2] for s in shapes}}
+    y = {n: torch.empty((tokens, n), dtype=bf, device=dev) for n in {s[2] for s in shapes}}
+    dx = {k: torch.empty((tokens, k), dtype=bf, device=dev) for k in {s[1] for s in shapes}}
+    ops, flop, keep, distinct = [], 0.0, [x, dy, y, dx], {}
+    planes = None       # fp32 partial planes of the K-sliced weight gradients (one buffer: the queue is in order)
+    for layer in range(n_layers):
+        for name, k, n in shapes:
+            w = inputs.bits_to_torch(inputs.normal_bits((k, n), [14, layer, k, n], 0.02), dev)
+            dw = torch.empty((k, n), dtype=bf, device=dev)
+            keep += [w, dw]
+            trio = [B.gemm_op(x[k], w, y[n], tokens, n, k),                       # Y  = X W
+                    B.gemm_op(dy[n], w, dx[k], tokens, k, n, tb=True),            # dX = dY W^T
+                    B.gemm_op(x[k], dy[n], dw, k, n, tokens, ta=True)]            # dW = X^T dY
+            # few output tiles, K = tokens: cut K so that every CU of the partition gets a tile
+            tile, slices = B.lithos_gemm_split_hint(trio[2], split_cus)
+            extra = []
+            if slices > 1:
+                if planes is None or planes.numel() < slices * k * n:     # grows during the first layer only
+                    planes = torch.empty(slices * k * n, dtype=torch.float32, device=dev)
+                    keep.append(planes)
+                trio[2] = B.gemm_op(x[k], dy[n], planes, k, n, tokens, ta=True, tile=tile, k_slices=slices)
+                extra = [B.sum_slices_op(planes, dw, k, n, slices)]
+            ops += trio + extra
+            flop += 3 * 2.0 * tokens * k * n
+            if layer == 0:
+                for kind, o in zip(("fwd", "dX", "dW"), trio):
+                    distinct["be_%s_%s" % (name, kind)] = (o, 2.0 * tokens * k * n)
+                if extra:
+                    distinct["be_%s_dW_sum" % name] = (extra[0], 0.0)
+    return ops, flop, keep, distinct

@@ -15,12 +15,12 @@ import torch
 
 from . import binding as B
 from . import inputs
-from .models import DecoderChain, EncoderChain, MlpChain
+from .models import DecoderChain, EncoderChain, MlpChain, training_block_ops
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "mlp", "skinny", "encoder", "decoder"])
+    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "mlp", "skinny", "encoder", "decoder", "train"])
     ap.add_argument("--tile", type=int, default=256)
     ap.add_argument("--batch", type=int, default=4)
     ap.add_argument("--layers", type=int, default=4)
@@ -58,6 +58,13 @@ def main():
         ops = chain.ops()
         if args.what == "skinny":
             ops = [o for o in ops if o.kind == B.OP_GEMM]
+        torch.cuda.synchronize()
+        for _ in range(args.reps):
+            for o in ops:
+                B.lithos_launch_atomized(ctx, o, (0, 0, 0), 0, part, None)
+        B.lithos_partition_sync(ctx, part)
+    elif args.what == "train":          # fwd, dX, dW GEMMs of --layers transformer blocks (hidden 1024, FFN 4096, 16384 tokens)
+        ops, _, keep, _ = training_block_ops(n_layers=args.layers, split_cus=args.cus)
         torch.cuda.synchronize()
         for _ in range(args.reps):
             for o in ops:
