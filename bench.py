@@ -21,6 +21,8 @@ Other workloads (same JSON layout, not the headline):
   --workload cfg5   decoder-layer decode (32 layers, hidden 4096, GQA 32/8, FFN 14336, KV 2048,
                     --batch) stacked with the cfg2 best-effort GEMM
   --workload cfg4   right-sizing sweep over every kernel of cfg3 (CU counts 8..256 step 8)
+  --workload atoms  atomization case study (paper Section 7.4): the cfg2 high-priority tenant against
+                    best-effort GEMMs of growing duration, kernel atomization off and on
 """
 from __future__ import annotations
 
@@ -193,7 +195,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "atoms"])
     ap.add_argument("--batch", type=int, default=8, help="cfg3/cfg5 high-priority batch size")
     ap.add_argument("--layers", type=int, default=32, help="cfg5 decoder layers")
     ap.add_argument("--atom-us", type=float, default=250.0)
@@ -214,6 +216,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.workload == "cfg4":
         return rightsize_sweep(args, B, inputs, torch)
+    if args.workload == "atoms":
+        return atomization_study(args, B, inputs, torch)
     K, W = args.steps, args.warmup
     wl = {"cfg2": wl_cfg2, "cfg3": wl_cfg3, "cfg5": wl_cfg5}[args.workload](args, B, inputs, torch)
     torch.cuda.synchronize()
@@ -341,6 +345,59 @@ def main():
 # ---------------------------------------------------------------------------------------------
 # cfg4: right-sizing sweep over every kernel of cfg3
 # ---------------------------------------------------------------------------------------------
+
+def atomization_study(args, B, inputs, torch):
+    """The longer the best-effort kernel, the longer an arriving high-priority request waits for the
+    CUs it lent - unless the kernel is cut into atoms (paper Section 7.4, atomization case study)."""
+    from paper_2504_15465_amd.models import MlpChain
+    layers = inputs.mlp_params(6, 4096, seed=1)
+    pool_bits = inputs.mlp_requests(pool=64, batch=8, hidden=4096, seed=2)
+    chain = MlpChain(layers, 8, "cuda")
+    pool = [inputs.bits_to_torch(pool_bits[i], "cuda").contiguous() for i in range(64)]
+    hp_requests = [chain.ops(x) for x in pool]
+    K, W = min(args.steps, 1500), min(args.warmup, 100)
+    arrivals = inputs.poisson_arrivals(200.0, W + K, seed=3)
+    rows = []
+    for m, n, k in ((4096, 4096, 4096), (8192, 8192, 8192), (16384, 16384, 8192), (16384, 16384, 16384)):
+        bf = torch.bfloat16
+        a = (torch.randn((m, k), device="cuda", generator=torch.Generator("cuda").manual_seed(4)) * 0.5).to(bf)
+        b = (torch.randn((k, n), device="cuda", generator=torch.Generator("cuda").manual_seed(5)) * 0.5).to(bf)
+        c = torch.empty((m, n), dtype=bf, device="cuda")
+        op = B.gemm_op(a, b, c, m, n, k, tile=256)
+        wl = dict(hp_requests=hp_requests, be=dict(ops=[op], flop=2.0 * m * n * k))
+        torch.cuda.synchronize()
+        row = {"be_gemm": "%dx%dx%d" % (m, n, k)}
+        for atomize in (0, 1):
+            cfg = B.Config.default(atom_duration_us=args.atom_us, max_outstanding=args.max_outstanding,
+                                   max_outstanding_hp=64, steal=1, atomize=atomize)
+            ctx, parts, t_hp, t_be = make_world(B, cfg)
+            if atomize == 0:
+                p_all = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 256, B.MASK_STRIPED, 0))
+                row["be_kernel_us_256cu"] = B.lithos_time_launch(ctx, op, 0, p_all, 2, 5)[1]
+                parts = parts + [p_all]
+            r = stacked_leg(B, torch, wl, t_hp, t_be, arrivals, W)
+            drop_world(B, ctx, parts, [t_hp, t_be])
+            lat = r["lat"]
+            row["atoms_on" if atomize else "atoms_off"] = {
+                "hp_p50_us": nearest_rank(lat, 0.5), "hp_p95_us": nearest_rank(lat, 0.95), "hp_p99_us": nearest_rank(lat, 0.99),
+                "be_tflops": r["be_iters"] * wl["be"]["flop"] / r["be_secs"] * 1e-12}
+        row["hp_p95_off_over_on"] = row["atoms_off"]["hp_p95_us"] / row["atoms_on"]["hp_p95_us"]
+        row["hp_p99_off_over_on"] = row["atoms_off"]["hp_p99_us"] / row["atoms_on"]["hp_p99_us"]
+        row["be_tflops_on_over_off"] = row["atoms_on"]["be_tflops"] / row["atoms_off"]["be_tflops"]
+        rows.append(row)
+        del a, b, c, op, wl
+        torch.cuda.empty_cache()
+    line = {"metric": "atomization case study: high-priority tail with best-effort kernels of growing duration, atoms off / on",
+            "value": rows[-1]["hp_p99_off_over_on"], "unit": "x lower HP p99 with atomization (longest BE kernel)",
+            "n_gpus": 1, "steps": K, "warmup": W, "higher_is_better": True, "data": "synthetic", "dtype": "bf16",
+            "config": {"workload": "atoms: cfg2 high-priority MLP (Poisson 200 req/s, 64-CU quota) + best-effort bf16 GEMMs "
+                                   "of growing size on 192 CUs, stealing on", "atom_duration_us": args.atom_us,
+                       "max_outstanding": args.max_outstanding},
+            "rows": rows,
+            "paper_context": "LithOS on A100: atomization lowers HP P95 2x (BE training batch sweep) and 1.3x (BE sequence sweep); "
+                             "10 % BE throughput cost"}
+    print(json.dumps(line))
+
 
 def rightsize_sweep(args, B, inputs, torch):
     import numpy as np
