@@ -95,12 +95,13 @@ class CoreHarness:
     """Plays clock and device for the C policy core exactly as the oracle's
     simulator plays them for its own policy (exclusive CU groups, stream order)."""
 
-    def __init__(self, cfg: B.Config, ops_by_kernel):
+    def __init__(self, cfg: B.Config, ops_by_kernel, tenants=None):
         self.c = B.lithos_core_create(cfg, 32, 8)
-        self.hp = B.lithos_core_add_tenant(self.c, B.CLASS_HP, _bits(HP_Q))
-        self.be = B.lithos_core_add_tenant(self.c, B.CLASS_BE, _bits(BE_Q))
+        tenants = tenants or [(B.CLASS_HP, HP_Q), (B.CLASS_BE, BE_Q)]
+        self.ids = [B.lithos_core_add_tenant(self.c, cls, _bits(q)) for cls, q in tenants]
+        self.hp, self.be = self.ids[0], self.ids[-1]
         self.group_free = [0.0] * 32
-        self.last_end = {self.hp: 0.0, self.be: 0.0}
+        self.last_end = {t: 0.0 for t in self.ids}
         self.events = []
         self.seq = 0
         self.trace = []
@@ -115,7 +116,7 @@ class CoreHarness:
         progressed = True
         while progressed:
             progressed = False
-            for t in (self.hp, self.be):
+            for t in self.ids:
                 a = B.lithos_core_next_atom(self.c, t, now)
                 if a is None:
                     continue
@@ -203,4 +204,62 @@ def test_policy_core_matches_oracle_model_step_by_step(atomize, steal, atom_us, 
     assert s_hp.stolen_atoms + s_be.stolen_atoms == sim.stats["steals"]
     assert s_hp.mispredicts + s_be.mispredicts == sim.stats["mispredicts"]
     assert s_hp.predictions + s_be.predictions == sim.stats["predictions"]
+    B.lithos_core_destroy(h.c)
+
+
+@pytest.mark.parametrize("atomize,steal", [(True, True), (False, True), (True, False)])
+def test_policy_core_matches_oracle_model_with_three_tenants(atomize, steal):
+    """Two high-priority tenants (quotas of 128 and 64 CUs) and a best-effort tenant with a small
+    quota (64 CUs) that lives on what the other two leave idle (paper Section 7.1, inference-only
+    stacking): the C core and the oracle's model take the same decisions, and a high-priority
+    tenant may also borrow the other one's idle CUs."""
+    quotas = [frozenset(range(0, 16)), frozenset(range(16, 24)), frozenset(range(24, 32))]
+    rnd = random.Random(7)
+    scenario = []
+    for i in range(40):
+        scenario.append((0.0, "submit", 2, 1024, "be"))
+        scenario.append((0.0, "sync", 2, 0, ""))
+    for t in sorted(rnd.uniform(100, 40000) for _ in range(30)):
+        scenario.append((t, "submit", 0, 256, "hp_a"))
+        scenario.append((t, "submit", 0, 64, "hp_b"))
+        scenario.append((t, "sync", 0, 0, ""))
+    for t in sorted(rnd.uniform(100, 40000) for _ in range(25)):
+        scenario.append((t, "submit", 1, 96, "hp_b"))
+        scenario.append((t, "sync", 1, 0, ""))
+    scenario.sort(key=lambda e: e[0])           # stable: same-time events keep their order
+
+    sim = Simulator(SimConfig(atom_duration_us=100.0, max_outstanding=2, max_outstanding_hp=4, steal=steal, atomize=atomize), _lat)
+    sim_ids = [sim.add_tenant(quotas[0], hp=True), sim.add_tenant(quotas[1], hp=True), sim.add_tenant(quotas[2], hp=False)]
+    for time, kind, who, total, op in scenario:
+        if kind == "submit":
+            sim.submit_at(time, sim_ids[who], Kernel(op, total, 1))
+        else:
+            sim.sync_at(time, sim_ids[who])
+    sim.run()
+    want = [(a.tenant, a.ordinal, a.lo, a.hi, _bits(a.mask), a.stolen, a.t_start, a.t_end) for a in sim.trace]
+
+    cfg = B.Config.default(atom_duration_us=100.0, max_outstanding=2, max_outstanding_hp=4, steal=int(steal), atomize=int(atomize))
+    h = CoreHarness(cfg, {}, [(B.CLASS_HP, quotas[0]), (B.CLASS_HP, quotas[1]), (B.CLASS_BE, quotas[2])])
+    for time, kind, who, total, op in scenario:
+        if kind == "submit":
+            h.push(time, "submit", (h.ids[who], total, op))
+        else:
+            h.push(time, "sync", h.ids[who])
+    h.run()
+    got = [(sim_ids[h.ids.index(t)], o, lo, hi, m, st, s, e) for t, o, lo, hi, m, st, _, s, e in h.trace]
+    assert len(got) == len(want)
+    for g, w in zip(got, want):
+        assert g[:6] == w[:6], (g, w)
+        assert abs(g[6] - w[6]) < 1e-9 and abs(g[7] - w[7]) < 1e-9
+    # no atom ever ran on CUs outside its tenant's quota plus quotas lent by an idle owner
+    for t, o, lo, hi, m, st, s, e in got:
+        own = _bits(quotas[sim_ids.index(t)])
+        assert m & own == own
+        assert st == (m != own)
+        if not steal:
+            assert m == own
+    if steal:
+        stolen_by = {t for t, *_rest in [(g[0], g[5]) for g in got if g[5]]}
+        assert sim_ids[2] in stolen_by                      # best effort lives on lent CUs
+        assert any(g[5] and g[0] in sim_ids[:2] for g in got)   # a high-priority tenant borrowed too
     B.lithos_core_destroy(h.c)

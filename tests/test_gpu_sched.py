@@ -150,3 +150,49 @@ def test_tenant_queues_do_not_share_a_command_processor_pipe():
         for p in parts:
             B.lithos_destroy_partition(p)
         B.lithos_shutdown(c)
+
+
+def test_three_tenants_bit_exact_with_stealing_between_all_of_them():
+    """Two high-priority tenants (128 and 64 CUs) and a best-effort tenant (64 CUs): every tenant's results
+    equal its solo results bit for bit while CUs move between all three at atom boundaries."""
+    cfg = B.Config.default(atom_duration_us=100.0, max_outstanding=2, max_outstanding_hp=16, steal=1, atomize=1)
+    c = B.lithos_init(0, cfg)
+    parts = [B.lithos_create_partition(c, B.lithos_make_mask(c, n, B.MASK_STRIPED, first)) for n, first in ((128, 0), (64, 128), (64, 192))]
+    ts = [B.lithos_tenant_create(c, cls, p) for cls, p in zip((B.CLASS_HP, B.CLASS_HP, B.CLASS_BE), parts)]
+    try:
+        m = 4096
+        a_bits, b_bits = inputs.gemm_operands(m, m, m, seed=4)
+        a, b = dev_bits(a_bits), dev_bits(b_bits)
+        c_ref, c_be = nan_like((m, m), torch.bfloat16), nan_like((m, m), torch.bfloat16)
+        torch.cuda.synchronize()
+        B.lithos_launch_atomized(c, B.gemm_op(a, b, c_ref, m, m, m, tile=256))
+        B.lithos_partition_sync(c, None)
+        be_op = B.gemm_op(a, b, c_be, m, m, m, tile=256)
+        chains = []
+        for seed in (1, 5):
+            ch = MlpChain(inputs.mlp_params(2, 1024, seed=seed), 8)
+            ch.set_input(inputs.mlp_requests(pool=1, batch=8, hidden=1024, seed=seed + 1)[0])
+            run_ops(c, ch.ops(), parts[0])
+            chains.append((ch, ch.out.clone(), ch.ops()))
+        torch.cuda.synchronize()
+        drv = B.lithos_drive_closed_loop_start(ts[2], [be_op], depth=2)
+        time.sleep(0.05)
+        for i in range(20):
+            for ch, _, _ in chains:
+                ch.out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            for t, (ch, ref, ops) in zip(ts[:2], chains):
+                for op in ops:
+                    B.lithos_submit(t, op)
+            for t, (ch, ref, ops) in zip(ts[:2], chains):
+                B.lithos_sync(t)
+                assert bits_equal(ch.out, ref), "request %d" % i
+            time.sleep(0.002)
+        iters, _ = B.lithos_drive_closed_loop_stop(drv)
+        B.lithos_sync(ts[2])
+        assert iters >= 3 and bits_equal(c_be, c_ref)
+        st = [B.lithos_tenant_stats(t) for t in ts]
+        assert st[0].kernels == 20 * len(chains[0][2]) and st[1].kernels == 20 * len(chains[1][2])
+        assert st[2].stolen_atoms > 0 and st[2].atoms > st[2].kernels
+    finally:
+        drop_world(c, parts, ts)
