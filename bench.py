@@ -298,6 +298,16 @@ def main():
     overhead_pct = (at_med - whole_med) / whole_med * 100.0
     achieved = flop / (whole_mean * 1e-6) * 1e-12
     drop_world(B, ctx, parts + [p_all], [t_hp, t_be])
+    # the same atoms in the paper's Prelude form (every atom launches the whole grid, blocks outside
+    # the range exit at once): the early-exit traffic the remapping form avoids
+    ctx_p = B.lithos_init(0, B.Config.default(prelude=1))
+    p_all = B.lithos_create_partition(ctx_p, B.lithos_make_mask(ctx_p, 256, B.MASK_STRIPED, 0))
+    B.lithos_time_launch(ctx_p, op, 0, p_all, 3, 3)
+    rounds_p = [(B.lithos_time_launch(ctx_p, op, 0, p_all, 1, 5)[1], B.lithos_time_launch(ctx_p, op, atom_blocks, p_all, 1, 5)[1])
+                for _ in range(4)]
+    prelude_pct = (float(np.median([a for _, a in rounds_p])) / float(np.median([w for w, _ in rounds_p])) - 1.0) * 100.0
+    B.lithos_destroy_partition(p_all)
+    B.lithos_shutdown(ctx_p)
 
     cpu = None if args.no_cpu_baseline else wl["cpu_baseline"]()
 
@@ -330,7 +340,8 @@ def main():
         "aggregate_throughput_normalised": agg,
         "atom_overhead_pct": overhead_pct,
         "atom_overhead_detail": {"atom_blocks": atom_blocks, "total_blocks": total_blocks,
-                                 "whole_us": whole_med, "atomized_us": at_med, "cus": 256},
+                                 "whole_us": whole_med, "atomized_us": at_med, "cus": 256,
+                                 "prelude_form_overhead_pct": prelude_pct},
         "scheduler": {"be_atoms": int(s1.atoms - s0.atoms), "be_kernels": int(s1.kernels - s0.kernels),
                       "be_stolen_atoms": int(s1.stolen_atoms - s0.stolen_atoms),
                       "be_mispredict_rate": (s1.mispredicts / s1.predictions) if s1.predictions else None,

@@ -138,6 +138,11 @@ typedef struct lithos_config {
     int32_t  steal;              /* Section 4.3 'TPC Stealing' on/off; default 1 */
     int32_t  atomize;            /* Section 4.4 on/off; default 1 */
     int32_t  xcd_remap;          /* logical-block remap that undoes round-robin XCD placement; default 1 */
+    int32_t  prelude;            /* Algorithm 1 as printed: every atom launches the WHOLE grid and the blocks
+                                    outside [lo,hi) exit at once (what a kernel the library does not own
+                                    would need); default 0 = an atom launches exactly hi-lo workgroups that
+                                    remap themselves.  Same results bit for bit; kept to measure the
+                                    early-exit traffic of Section 4.4 'Performance Optimizations' */
     double   ema_alpha;          /* Section 4.7 predictor smoothing; default 0.25 */
 } lithos_config_t;
 

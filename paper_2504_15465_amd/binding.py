@@ -41,11 +41,11 @@ class Op(C.Structure):
 class Config(C.Structure):
     _fields_ = [("atom_duration_us", C.c_double), ("max_outstanding", C.c_int32),
                 ("max_outstanding_hp", C.c_int32), ("steal", C.c_int32), ("atomize", C.c_int32),
-                ("xcd_remap", C.c_int32), ("ema_alpha", C.c_double)]
+                ("xcd_remap", C.c_int32), ("prelude", C.c_int32), ("ema_alpha", C.c_double)]
 
     @classmethod
     def default(cls, **kw):
-        c = cls(250.0, 2, 0, 1, 1, 1, 0.25)
+        c = cls(250.0, 2, 0, 1, 1, 1, 0, 0.25)
         for k, v in kw.items():
             setattr(c, k, v)
         return c

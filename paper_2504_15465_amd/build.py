@@ -36,10 +36,23 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
+def _fresh(src: str) -> bool:
+    """Object newer than its source and every header (only consulted by --incremental)."""
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    if not os.path.exists(obj):
+        return False
+    deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    deps.append(os.path.join(HERE, "..", "include", "lithos.h"))
+    return all(os.path.getmtime(obj) > os.path.getmtime(d) for d in deps)
+
+
+def build(verbose: bool = True, incremental: bool = False) -> str:
+    """Compile every source (always, unless ``incremental``) and link the library."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+    todo = [s for s in SOURCES if not (incremental and _fresh(s))]
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(todo)))) as ex:
+        list(ex.map(_compile, todo))
+    objs = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES]
     tmp = LIB + ".tmp.%d" % os.getpid()
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs + ["-lpthread"],
                        capture_output=True, text=True)
@@ -52,5 +65,5 @@ def build(verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    build()
+    build(incremental="--incremental" in sys.argv[1:])
     sys.exit(0)

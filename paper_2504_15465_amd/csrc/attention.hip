@@ -455,7 +455,7 @@ int attn_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     a.o = op.out[0];
     a.scale = op.fparam[0];
     a.flags = op.flags;
-    const dim3 grid(atom.n), block(256);
+    const dim3 grid(LITHOS_ATOM_LAUNCH_BLOCKS(atom)), block(256);
     if (op.kind == LITHOS_OP_ATTN_ENC) {
         a.batch = (int)op.dim[0]; a.n_q = (int)op.dim[1]; a.seq = (int)op.dim[2]; a.d = (int)op.dim[3];
         attn_fn fn = a.seq == 64 ? (attn_fn)attn_enc_kernel<2> : a.seq == 128 ? (attn_fn)attn_enc_kernel<4> : (attn_fn)attn_enc_kernel<8>;

@@ -127,7 +127,7 @@ int gemm_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     g.k_slices = (int)op.dim[5]; g.c_slice = op.dim[6];
     gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B, op.flags & LITHOS_F_IN_F32,
                             op.flags & LITHOS_F_SPLIT_A, staged_epilogue(op));
-    LITHOS_HIP(launch_kernel(fn, dim3(atom.n), dim3(plan.threads), s, g, atom));
+    LITHOS_HIP(launch_kernel(fn, dim3(LITHOS_ATOM_LAUNCH_BLOCKS(atom)), dim3(plan.threads), s, g, atom));
     return LITHOS_OK;
 }
 

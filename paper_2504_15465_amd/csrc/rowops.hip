@@ -542,7 +542,7 @@ int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& ato
 {
     RowArgs a = make_args(op);
     const bool in32 = op.flags & LITHOS_F_IN_F32, out32 = op.flags & LITHOS_F_OUT_F32;
-    const dim3 grid(atom.n), block(plan.threads);
+    const dim3 grid(LITHOS_ATOM_LAUNCH_BLOCKS(atom)), block(plan.threads);
     hipError_t e = hipSuccess;
 #define L2(K, A, B) e = launch_kernel(K<A, B>, grid, block, s, a, atom)
 #define L3(K, A, B, C) e = launch_kernel(K<A, B, C>, grid, block, s, a, atom)

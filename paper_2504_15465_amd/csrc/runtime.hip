@@ -163,6 +163,7 @@ void default_config(lithos_config_t* c)
     c->steal = 1;
     c->atomize = 1;
     c->xcd_remap = 1;
+    c->prelude = 0;
     c->ema_alpha = 0.25;
 }
 
@@ -424,7 +425,10 @@ AtomArgs make_atom(const lithos_ctx* ctx, const OpPlan& plan, uint32_t lo, uint3
     a.n = hi - lo;
     a.gx = plan.grid.x;
     a.gy = plan.grid.y;
-    a.n_xcd = (ctx->cfg.xcd_remap && n_dies > 1) ? (uint32_t)n_dies : 1u;
+    a.full = ctx->cfg.prelude ? plan.total : 0u;
+    // Algorithm 1 as printed numbers blocks by their hardware index; the die-aware remap belongs to the
+    // default form (over a whole grid it would hand an atom's contiguous range to one or two dies only)
+    a.n_xcd = (ctx->cfg.xcd_remap && n_dies > 1 && !a.full) ? (uint32_t)n_dies : 1u;
     a.counters = ctx->counters;
     return a;
 }

@@ -90,7 +90,7 @@ static int queues_coupled(lithos_ctx* ctx, hipStream_t busy, int busy_cus, hipSt
     int rc = op_plan(big, &pb);
     if (rc == LITHOS_OK) rc = op_plan(tiny, &pt);
     if (rc != LITHOS_OK) return rc;
-    AtomArgs ab{0, pb.total, pb.grid.x, pb.grid.y, 1, nullptr}, at{0, 1, 1, 1, 1, nullptr};
+    AtomArgs ab{0, pb.total, pb.grid.x, pb.grid.y, 1, 0, nullptr}, at{0, 1, 1, 1, 1, 0, nullptr};
     LITHOS_HIP(hipStreamSynchronize(busy));
     LITHOS_HIP(hipStreamSynchronize(probe));
     rc = op_launch(big, pb, ab, busy);

@@ -47,6 +47,7 @@ def test_binding_struct_sizes_match_the_header_layout():
     import ctypes as C
     assert C.sizeof(B.Op) == 4 * 4 + 8 * 8 + 4 * 8 + 4 * 4 + 6 * 8 + 2 * 8
     assert C.sizeof(B.Dim3) == 12
+    assert C.sizeof(B.Config) == 40
     assert C.sizeof(B.CoreAtom) == 56
     assert C.sizeof(B.Stats) == 48
 

@@ -4,9 +4,11 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import ops as O
 from oracle import rightsize as R
 from paper_2504_15465_amd import binding as B
-from gpu_util import ctx
+from paper_2504_15465_amd import inputs
+from gpu_util import bits_equal, counters, ctx, dev_bits, nan_like, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -82,3 +84,39 @@ def test_rightsize_sweep_on_a_spin_kernel_and_selection_rule():
     assert abs(m / cus[0] + b - lat[0]) < 1e-6 * lat[0] and abs(m / cus[-1] + b - lat[-1]) < 1e-6 * lat[-1]
     with pytest.raises(B.LithosError):
         B.lithos_rightsize(c, op, 8, 512, 8, 1, 3, 0.04)
+
+
+def test_prelude_form_of_algorithm_1_gives_the_same_bits():
+    """Every atom launches the whole grid and blocks outside its range leave at once (the paper's
+    Prelude): same results bit for bit as the remapping form, each block still runs exactly once."""
+    from paper_2504_15465_amd.models import MlpChain, run_ops
+    m, n, k = 520, 776, 320
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=3)
+    a, b = dev_bits(a_bits), dev_bits(b_bits)
+    outs = {}
+    for prelude in (0, 1):
+        c = B.lithos_init(0, B.Config.default(prelude=prelude))
+        part = B.lithos_create_partition(c, B.lithos_make_mask(c, 64))
+        try:
+            for tile, atom_blocks in ((64, 7), (256, 1), (128, 0)):
+                out = nan_like((m, n), torch.float32)
+                op = B.gemm_op(a, b, out, m, n, k, tile=tile)
+                grid, _ = B.lithos_op_grid(c, op)
+                cnt = counters(grid[0] * grid[1])
+                B.lithos_debug_block_counters(c, cnt)
+                torch.cuda.synchronize()
+                B.lithos_launch_atomized(c, op, (0, 0, 0), atom_blocks, part, None)
+                B.lithos_partition_sync(c, part)
+                B.lithos_debug_block_counters(c, None)
+                assert cnt.cpu().tolist() == [1] * (grid[0] * grid[1])
+                outs[(prelude, tile)] = out
+            chain = MlpChain(inputs.mlp_params(2, 1024, seed=1), 8)          # row kernels and the skinny GEMM
+            chain.set_input(inputs.mlp_requests(pool=1, batch=8, hidden=1024, seed=2)[0])
+            run_ops(c, chain.ops(), part, atom_blocks=3)
+            outs[(prelude, "mlp")] = chain.out.clone()
+        finally:
+            B.lithos_destroy_partition(part)
+            B.lithos_shutdown(c)
+    for key in ((64,), (256,), (128,), ("mlp",)):
+        assert bits_equal(outs[(0,) + key], outs[(1,) + key])
+    assert rel_fro(outs[(1, 256)], O.gemm(a_bits, b_bits)) <= 1e-4
