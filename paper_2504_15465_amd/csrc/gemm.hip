@@ -89,6 +89,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         if (split) return fail(LITHOS_EINVAL, "gemm: the skinny kernel takes fp32 activations instead of SPLIT_A");
         if (slices > 1) return fail(LITHOS_EINVAL, "gemm: the skinny kernel splits K inside the workgroup; K slices need a tile kernel");
         if (M > 32 || !tb || ta) return fail(LITHOS_EINVAL, "gemm: the skinny kernel needs M <= 32, TRANS_B and no TRANS_A");
+        if (N * ldb * 2 >= (1ll << 32)) return fail(LITHOS_EINVAL, "gemm: the skinny kernel addresses weight rows with 32-bit byte offsets (N*ldb*2 < 4 GiB)");
         if (a32 && (lda % 4)) return fail(LITHOS_EINVAL, "gemm: fp32 activations need lda %% 4 == 0");
         variant = V_SKINNY32;
         if (M <= 16) variant = M <= 4 ? V_SKL4 : M <= 8 ? V_SKL8 : V_SKL16;

@@ -175,7 +175,12 @@ void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
 // cycles as the weights.  Here a wavefront loads only the live rows of its
 // next K chunk (coalesced), splits them once and keeps the three bf16 planes in
 // its own piece of LDS, from which the operands are read; rows beyond MR read
-// one shared row of zeros.  Weights go global -> registers -> MFMA as before.
+// one shared row of zeros.
+// Weights: a load instruction fetches whole 256-byte pieces of 4 weight rows (lane l:
+// row l/16, 16-byte chunk l%16) rather than the operand layout's 64-byte pieces of 16
+// rows - on a 64-CU partition the short pieces stream at 1.2 TB/s, the long ones at
+// 1.8-3.5 - and a 16-row block changes layout through the wavefront's own LDS piece
+// (write as loaded, read back as MFMA fragments) before it is multiplied.
 __device__ __forceinline__ void wave_lds_sync()
 {
     // LDS operations of one wavefront complete in order; this only stops the compiler
@@ -194,22 +199,24 @@ struct SkinnyChunk {
     uint4 wv[CH][NB];
     uint4 xv[NX];
 
-    // kc0 = first k of the chunk; dead = chunk index beyond the slice
-    __device__ __forceinline__ void load(const GemmArgs& g, const uint16_t* const (&wrow)[NB], int kc0, int kend, bool dead,
-                                         int lane, int kg)
+    static constexpr int CPRW = CH * 4;             // 16-byte chunks of a weight row per chunk of K
+    static constexpr int RPI = 64 / CPRW;           // weight rows per load instruction
+
+    // kc0 = first k of the chunk; dead = chunk index beyond the slice.  woff[u][j] = byte offset of
+    // the weight row that instruction u of 16-row block j reads for this lane (row u*RPI + lane/CPRW).
+    __device__ __forceinline__ void load(const GemmArgs& g, const uint32_t (&woff)[CH][NB], int kc0, int kend, bool dead, int lane)
     {
         const uint4 zero = make_uint4(0, 0, 0, 0);
+        const int k = kc0 + (lane % CPRW) * 8;
+        const bool klive = !dead && k < kend;
+        const char* wk = reinterpret_cast<const char*>(g.B) + (size_t)min(k, g.K - 8) * 2;
 #pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int k = kc0 + u * 32 + kg * 8;
-            const bool klive = !dead && k < kend;
-            const int kc = min(k, g.K - 8);
+        for (int u = 0; u < CH; ++u)
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
-                const uint4 v = *reinterpret_cast<const uint4*>(wrow[j] + kc);
+                const uint4 v = *reinterpret_cast<const uint4*>(wk + woff[u][j]);
                 wv[u][j] = klive ? v : zero;
             }
-        }
 #pragma unroll
         for (int i = 0; i < NX; ++i) {
             const int f = (i * 64 + lane) * EPL;
@@ -220,6 +227,26 @@ struct SkinnyChunk {
             if constexpr (A32) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(g.A) + at);
             else v = *reinterpret_cast<const uint4*>(g.A + at);
             xv[i] = live ? v : zero;
+        }
+    }
+
+    // Loaded layout (instruction u: rows u*RPI + lane/CPRW, chunk lane%CPRW) -> MFMA layout (fragment u:
+    // row lane%16, chunk 4u + lane/16) through `scr` (16 rows x CPRW chunks, chunk c of row r at c ^ (r % CPRW)).
+    __device__ __forceinline__ void to_fragments(uint16_t* scr, int lane)
+    {
+        const int cc = lane % CPRW, rr0 = lane / CPRW, r16 = lane & 15, kg = lane >> 4;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                const int rr = u * RPI + rr0;
+                *reinterpret_cast<uint4*>(scr + (rr * CPRW + (cc ^ (rr % CPRW))) * 8) = wv[u][j];
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int u = 0; u < CH; ++u)
+                wv[u][j] = *reinterpret_cast<const uint4*>(scr + (r16 * CPRW + ((4 * u + kg) ^ (r16 % CPRW))) * 8);
+            wave_lds_sync();
         }
     }
 
@@ -278,7 +305,7 @@ struct SkinnyChunk {
 };
 
 template <int MR, int NB, int CH, bool A32>
-__global__ __launch_bounds__(SKINNY_WAVES * 64)
+__global__ __launch_bounds__(SKINNY_WAVES * 64, 4)      // 128 registers: two workgroups per CU
 void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
 {
     constexpr int KW = SKINNY_WAVES;
@@ -286,7 +313,8 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
     constexpr int ROW = KC + 8;                      // padded row: 16 rows read 16 B each without bank conflicts
     constexpr int PL = (MR + 1) * ROW;               // one plane: MR rows and the row of zeros
     constexpr int NPL = A32 ? 3 : 1;                 // bf16 activations need no splitting
-    constexpr int XBYTES = KW * NPL * PL * 2;
+    constexpr int XW = NPL * PL * 2 > CH * 1024 ? NPL * PL * 2 : CH * 1024;   // a wavefront's piece: activation planes, or one
+    constexpr int XBYTES = KW * XW;                                           // 16-row weight block while it changes layout
     constexpr int RBYTES = KW * NB * 64 * 16;
     __shared__ __attribute__((aligned(16))) unsigned char smem[XBYTES > RBYTES ? XBYTES : RBYTES];
 
@@ -298,17 +326,23 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
     const int kq = ((g.K + 32 * KW - 1) / (32 * KW)) * 32;
     const int kbeg = wave * kq, kend = min(g.K, kbeg + kq);
 
-    uint16_t* xs = reinterpret_cast<uint16_t*>(smem) + wave * NPL * PL;
-    for (int t = lane; t < NPL * (ROW / 4); t += 64) // the row of zeros of each plane
-        *reinterpret_cast<uint2*>(xs + (t / (ROW / 4)) * PL + MR * ROW + (t % (ROW / 4)) * 4) = make_uint2(0, 0);
+    uint16_t* xs = reinterpret_cast<uint16_t*>(smem + wave * XW);
+    auto zero_rows = [&]() {                         // the row of zeros of each plane (the weight blocks pass over it)
+        for (int t = lane; t < NPL * (ROW / 4); t += 64)
+            *reinterpret_cast<uint2*>(xs + (t / (ROW / 4)) * PL + MR * ROW + (t % (ROW / 4)) * 4) = make_uint2(0, 0);
+    };
     const uint16_t* xrow = xs + min(r16, MR) * ROW;
 
     f32x4 acc[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const uint16_t* wrow[NB];
+    typedef SkinnyChunk<MR, NB, CH, A32> Chunk;
+    uint32_t woff[CH][NB];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) wrow[j] = g.B + (int64_t)min(n0 + j * 16 + r16, g.N - 1) * g.ldb + 0;
+    for (int u = 0; u < CH; ++u)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            woff[u][j] = (uint32_t)((int64_t)min(n0 + j * 16 + u * Chunk::RPI + lane / Chunk::CPRW, g.N - 1) * g.ldb * 2);
 
     // chunks are walked cyclically from a per-workgroup start so that workgroups, whose weight
     // rows are a power-of-two stride apart, do not address the same memory channels together
@@ -316,25 +350,29 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
     int ci = (int)((L * 7u + (uint32_t)wave * 3u) % (uint32_t)nch);
     auto next_chunk = [&](int& kc0) { kc0 = kbeg + ci * KC; ci = ci + 1 == nch ? 0 : ci + 1; };
 
-    SkinnyChunk<MR, NB, CH, A32> c0, c1;
+    Chunk c0, c1;
+    // a chunk's weights change layout in the piece of LDS that its activations then occupy
+    auto settle = [&](Chunk& c) {
+        c.to_fragments(xs, lane);
+        zero_rows();
+        c.template stage<ROW, PL>(xs, lane);
+        wave_lds_sync();
+    };
     int kc0;
     next_chunk(kc0);
-    c0.load(g, wrow, kc0, kend, false, lane, kg);
-    c0.template stage<ROW, PL>(xs, lane);
-    wave_lds_sync();
+    c0.load(g, woff, kc0, kend, false, lane);
+    settle(c0);
     for (int c = 0; c < nch; c += 2) {
         next_chunk(kc0);
-        c1.load(g, wrow, kc0, kend, c + 1 >= nch, lane, kg);
+        c1.load(g, woff, kc0, kend, c + 1 >= nch, lane);
         c0.template compute<ROW, PL>(xrow, kg, acc);
         wave_lds_sync();
-        c1.template stage<ROW, PL>(xs, lane);
-        wave_lds_sync();
+        settle(c1);
         next_chunk(kc0);
-        c0.load(g, wrow, kc0, kend, c + 2 >= nch, lane, kg);
+        c0.load(g, woff, kc0, kend, c + 2 >= nch, lane);
         c1.template compute<ROW, PL>(xrow, kg, acc);
         wave_lds_sync();
-        c0.template stage<ROW, PL>(xs, lane);
-        wave_lds_sync();
+        settle(c0);
     }
 
     __syncthreads();                                  // the reduction buffer overlays the activations
