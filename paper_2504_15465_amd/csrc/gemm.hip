@@ -1,19 +1,24 @@
 // Atom-aware bf16 GEMM for gfx950: C = op(A) op(B) [+bias][GELU][+residual].
+// This file validates a GEMM descriptor, picks the kernel and launches one atom.
 //
-// Two kernel families:
-//  * gemm_tile_kernel  - MFMA (v_mfma_f32_32x32x16_bf16) on LDS-staged tiles of
-//    64x64, 128x128 or 256x256 outputs, BK = 64, 4 wavefronts per workgroup;
-//  * gemm_skinny_kernel - M <= 32 rows (bf16 or fp32 activations) against a
-//    [N,K] bf16 weight matrix: HBM-bound, the weights are streamed exactly
-//    once with 16-byte loads.  The products still go through MFMA 16x16x32
-//    (weights as the row operand, activations padded to 16 rows): on a 64-CU
-//    partition the plain vector ALUs would need longer for the 2*M*N*K flops
-//    than HBM needs for the weights.
+// Kernel families (one translation unit each):
+//  * gemm_lds256_kernel (gemm_lds256.hip) - 256x256 tiles, K % 64 == 0, any operand
+//    layout: global memory straight into LDS, k-strided operands read with the
+//    transposing LDS load; the best-effort and training-shaped GEMMs;
+//  * gemm_tile_kernel (gemm_tile.hpp, gemm_tile{64,128,256}.hip) - 64/128/256
+//    tiles through registers, ragged K, split-bf16 A;
+//  * gemm_skinny_*_kernel (gemm_skinny.hip) - M <= 32 rows (bf16 or fp32
+//    activations) against a [N,K] bf16 weight matrix: HBM-bound, the weights are
+//    streamed exactly once.  The products still go through MFMA 16x16x32
+//    (weights as the row operand): on a 64-CU partition the plain vector ALUs
+//    would need longer for the 2*M*N*K flops than HBM needs for the weights.
 //
 // Every workgroup computes the output tile named by its LOGICAL block index
 // (LithOS Section 4.4), so a launch of any sub-range of blocks writes exactly
-// what the full launch writes for those tiles.  No split-K, no atomics: each
-// tile's arithmetic depends only on its logical index.
+// what the full launch writes for those tiles.  No atomics; a K that is cut
+// into slices (dim[5]) puts the slice on the logical grid's z axis and writes
+// one fp32 plane per slice, which SUM_SLICES adds in slice order: each block's
+// arithmetic depends only on its logical index.
 #include "gemm_common.hpp"
 
 namespace lithos {
