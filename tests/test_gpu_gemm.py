@@ -122,9 +122,12 @@ def test_exactly_representable_data_matches_oracle_bit_for_bit():
     assert bool((c == 1024.0).all())
 
 
-@pytest.mark.parametrize("tile,tb", [(64, False), (128, True), (B.TILE_SKINNY, True)])
-def test_fused_epilogue_bias_gelu_residual(tile, tb):
-    m, n, k = (24, 200, 264) if tile == B.TILE_SKINNY else (136, 200, 264)
+@pytest.mark.parametrize("tile,tb,k", [(64, False, 264), (128, True, 264), (B.TILE_SKINNY, True, 264),
+                                       (256, False, 320), (256, True, 320), (256, False, 264)])
+def test_fused_epilogue_bias_gelu_residual(tile, tb, k):
+    """Bias, GELU and residual in the epilogue, fp32 and bf16 C; full tiles (through LDS, or 16 bytes per
+    lane for fp32) and ragged edge tiles (element by element) must agree with the oracle alike."""
+    m, n = (24, 200) if tile == B.TILE_SKINNY else (136, 200) if tile < 256 else (520, 776)
     a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=9, tb=tb)
     bias = inputs.normal_f32((n,), 10, 0.5)
     resid = inputs.normal_f32((m, n), 11, 1.0)
