@@ -31,7 +31,7 @@ static int tile_threads(int variant) { return (variant == 30 || variant == 31) ?
 // (fp32 tiles of the same kernels are stored from registers, 16 bytes per lane)
 static bool staged_epilogue(const lithos_op_t& op)
 {
-    if (op.flags & (LITHOS_F_OUT_SPLIT | LITHOS_F_SPLIT_A)) return false;
+    if ((op.flags & LITHOS_F_OUT_SPLIT) && op.dim[4] % 8) return false;
     if (op.flags & LITHOS_F_OUT_F32) return op.ld[2] % 4 == 0 && op.dim[6] % 4 == 0 && aligned16(op.out[0]);
     return op.ld[2] % 8 == 0 && aligned16(op.out[0]);
 }

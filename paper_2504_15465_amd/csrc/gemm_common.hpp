@@ -108,26 +108,49 @@ __device__ __forceinline__ int stage_index(int r, int p)
 
 // accumulator block with exchanged operands: lane holds output row (lane & 31) of the
 // block and columns 8*q + 4*(lane >> 5) + t, q = 0..3, t = 0..3
-template <int BN>
-__device__ __forceinline__ void stage_block(const GemmArgs& g, uint16_t* st, int r, int m, int n_tile, int n_glob,
-                                            const f32x16& acc, int lane)
+
+// bias, GELU and residual applied in place (a no-op without those flags)
+__device__ __forceinline__ void epilogue_block_swapped(const GemmArgs& g, int m, int n_glob, f32x16& acc, int lane)
 {
-    const bool plain = !(g.flags & (LITHOS_F_BIAS | LITHOS_F_GELU | LITHOS_F_RESIDUAL));   // uniform
+    if (!(g.flags & (LITHOS_F_BIAS | LITHOS_F_GELU | LITHOS_F_RESIDUAL))) return;   // uniform
+    static_for<16>([&](auto ee) {
+        constexpr int e = decltype(ee)::value;
+        const int n = n_glob + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        float v = acc[e];
+        if (g.flags & LITHOS_F_BIAS) v += g.bias[n];
+        if (g.flags & LITHOS_F_GELU) v = gelu_erf(v);
+        if (g.flags & LITHOS_F_RESIDUAL) v += g.resid[(int64_t)m * g.ldr + n];
+        acc[e] = v;
+    });
+}
+
+// the block's values rounded to bf16 into the staged tile; LO: what the first rounding dropped,
+// bf16(v - bf16(v)), the second plane of a split-bf16 output
+template <int BN, bool LO>
+__device__ __forceinline__ void stage_block_values(uint16_t* st, int r, int n_tile, const f32x16& acc, int lane)
+{
     static_for<4>([&](auto qq) {
         constexpr int q = decltype(qq)::value;
         const int nl = n_tile + 8 * q + 4 * (lane >> 5);
-        const int n = n_glob + 8 * q + 4 * (lane >> 5);
         uint16_t h[4];
-        if (plain) {
-            h[0] = f32_to_bf16_rne(acc[4 * q]);     h[1] = f32_to_bf16_rne(acc[4 * q + 1]);
-            h[2] = f32_to_bf16_rne(acc[4 * q + 2]); h[3] = f32_to_bf16_rne(acc[4 * q + 3]);
-        } else {
-            h[0] = epilogue_bf16(g, m, n, acc[4 * q]);         h[1] = epilogue_bf16(g, m, n + 1, acc[4 * q + 1]);
-            h[2] = epilogue_bf16(g, m, n + 2, acc[4 * q + 2]); h[3] = epilogue_bf16(g, m, n + 3, acc[4 * q + 3]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float v = acc[4 * q + t];
+            h[t] = f32_to_bf16_rne(v);
+            if constexpr (LO) h[t] = f32_to_bf16_rne(v - __uint_as_float((uint32_t)h[t] << 16));
         }
         *reinterpret_cast<uint2*>(st + stage_index<BN>(r, nl >> 3) + (nl & 4)) =
             make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
     });
+}
+
+template <int BN>
+__device__ __forceinline__ void stage_block(const GemmArgs& g, uint16_t* st, int r, int m, int n_tile, int n_glob,
+                                            const f32x16& acc, int lane)
+{
+    f32x16 v = acc;
+    epilogue_block_swapped(g, m, n_glob, v, lane);
+    stage_block_values<BN, false>(st, r, n_tile, v, lane);
 }
 
 // the same block of a full fp32 tile: 16 bytes (four columns) per lane and store

@@ -178,7 +178,7 @@ void gemm_lds256_kernel(GemmArgs g, AtomArgs atom)
                 store_block_swapped_f32(g, reinterpret_cast<float*>(g.C), m0 + wm * WM + i * 32 + (lane & 31),
                                         n0 + wn * WN + j * 32, acc[i][j], lane);
             });
-        } else if (m0 + BM <= g.M && n0 + BN <= g.N) {
+        } else if (m0 + BM <= g.M && n0 + BN <= g.N && !(g.flags & LITHOS_F_OUT_SPLIT)) {
             __syncthreads();
             static_for<MI * NI>([&](auto ij) {
                 constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;

@@ -104,7 +104,6 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 {
     constexpr int T = WGM * WGN * 64, BK = 64;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
-    static_assert(!(ST && SPLIT), "the staged epilogue writes a single bf16 plane");
     // operand buffers; a staged epilogue needs room for the whole bf16 output tile
     constexpr int OPERAND_ELEMS = (BM + BN) * BK + (SPLIT ? BM * BK : 0);
     __shared__ __attribute__((aligned(16))) uint16_t smem[ST && BM * BN > OPERAND_ELEMS ? BM * BN : OPERAND_ELEMS];
@@ -173,7 +172,9 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
-                    if constexpr (SPLIT)    // small term first
+                    if constexpr (SPLIT && ST)    // small term first
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af2[i], acc[i][j], 0, 0, 0);
+                    else if constexpr (SPLIT)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af2[i], bfr[j], acc[i][j], 0, 0, 0);
                     if constexpr (ST)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
@@ -204,15 +205,26 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
             static_for<MI * NI>([&](auto ij) {
                 constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
                 const int rb = wm * WM + i * 32;
-                stage_block<BN>(g, smem, rb + (lane & 31), m0 + rb + (lane & 31), wn * WN + j * 32, n0 + wn * WN + j * 32,
-                                acc[i][j], lane);
+                epilogue_block_swapped(g, m0 + rb + (lane & 31), n0 + wn * WN + j * 32, acc[i][j], lane);
+                stage_block_values<BN, false>(smem, rb + (lane & 31), wn * WN + j * 32, acc[i][j], lane);
             });
-            __syncthreads();
+            auto store_tile = [&](uint16_t* dst) {
+                __syncthreads();
 #pragma unroll 4
-            for (int c = tid; c < BM * PPR; c += T) {
-                const int r = c / PPR, p = c % PPR;
-                const uint4 v = *reinterpret_cast<const uint4*>(smem + stage_index<BN>(r, p));
-                *reinterpret_cast<uint4*>(C + (int64_t)(m0 + r) * g.ldc + n0 + p * 8) = v;
+                for (int c = tid; c < BM * PPR; c += T) {
+                    const int r = c / PPR, p = c % PPR;
+                    const uint4 v = *reinterpret_cast<const uint4*>(smem + stage_index<BN>(r, p));
+                    *reinterpret_cast<uint4*>(dst + (int64_t)(m0 + r) * g.ldc + n0 + p * 8) = v;
+                }
+            };
+            store_tile(C);
+            if (g.flags & LITHOS_F_OUT_SPLIT) {          // second plane: what the bf16 rounding dropped
+                __syncthreads();
+                static_for<MI * NI>([&](auto ij) {
+                    constexpr int i = decltype(ij)::value / NI, j = decltype(ij)::value % NI;
+                    stage_block_values<BN, true>(smem, wm * WM + i * 32 + (lane & 31), wn * WN + j * 32, acc[i][j], lane);
+                });
+                store_tile(C + g.c_plane);
             }
         } else {
             static_for<MI * NI>([&](auto ij) {
@@ -242,8 +254,9 @@ void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
         : (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, WGM, WGN, false, true, false, ST>           \
               : (gemm_fn)gemm_tile_kernel<BMN, BMN, WGM, WGN, false, false, false, ST>))
 #define LITHOS_TILE_PICK(BMN, WGM, WGN) (st ? LITHOS_TILE_PICK4(BMN, WGM, WGN, true) : LITHOS_TILE_PICK4(BMN, WGM, WGN, false))
-#define LITHOS_TILE_PICK_SPLIT(BMN)                                                             \
-    (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, 2, 2, false, true, true, false>                   \
-        : (gemm_fn)gemm_tile_kernel<BMN, BMN, 2, 2, false, false, true, false>)
+#define LITHOS_TILE_PICK_SPLIT4(BMN, ST)                                                        \
+    (tb ? (gemm_fn)gemm_tile_kernel<BMN, BMN, 2, 2, false, true, true, ST>                      \
+        : (gemm_fn)gemm_tile_kernel<BMN, BMN, 2, 2, false, false, true, ST>)
+#define LITHOS_TILE_PICK_SPLIT(BMN) (st ? LITHOS_TILE_PICK_SPLIT4(BMN, true) : LITHOS_TILE_PICK_SPLIT4(BMN, false))
 
 } // namespace lithos
