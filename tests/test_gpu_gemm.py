@@ -352,3 +352,49 @@ def test_k_slices_bad_arguments():
     with pytest.raises(B.LithosError):      # the epilogue belongs to SUM_SLICES
         B.lithos_op_grid(ctx(), B.gemm_op(a, a, c32, 64, 64, 256, tb=True, tile=64, k_slices=4, gelu=True))
     assert B.lithos_op_grid(ctx(), B.gemm_op(a, a, c32, 64, 64, 256, tb=True, tile=64, k_slices=4))[0] == (1, 1, 4)
+
+
+def test_training_shapes_full_size_sampled_rows():
+    """The training-shaped tenant's GEMMs at full size in the launch shapes bench.py runs (16384 tokens,
+    hidden 1024): Y = X W and dX = dY W^T whole, dW = X^T dY cut along K as the split hint says and summed;
+    64 sampled rows of each result against the oracle, atomized launches bit-equal to whole ones."""
+    tokens, k, n = 16384, 1024, 3072
+    x_bits = inputs.normal_bits((tokens, k), [12, k])
+    dy_bits = inputs.normal_bits((tokens, n), [13, n])
+    w_bits = inputs.normal_bits((k, n), [14, 0, k, n], 0.02)
+    x, dy, w = dev_bits(x_bits), dev_bits(dy_bits), dev_bits(w_bits)
+    rng = np.random.default_rng(0)
+
+    def launch(op, atom_blocks):
+        torch.cuda.synchronize()
+        B.lithos_launch_atomized(ctx(), op, (0, 0, 0), atom_blocks, None, None)
+        B.lithos_partition_sync(ctx(), None)
+
+    # forward and input gradient: bf16 outputs
+    for name, a_bits, b_bits, a, b, m_, n_, k_, tb in (("fwd", x_bits, w_bits, x, w, tokens, n, k, False),
+                                                         ("dX", dy_bits, w_bits, dy, w, tokens, k, n, True)):
+        outs = []
+        for atom_blocks in (0, 256):
+            c = nan_like((m_, n_), torch.bfloat16)
+            launch(B.gemm_op(a, b, c, m_, n_, k_, tb=tb), atom_blocks)
+            outs.append(c)
+        assert bits_equal(outs[0], outs[1]), name
+        rows = np.sort(rng.choice(m_, 64, replace=False))
+        ref = O.gemm(a_bits[rows], b_bits, tb=tb)
+        bf16_close(outs[0][torch.from_numpy(rows).cuda()], ref, abs_tol=2.0 ** -22 * k_ * 4)
+    # weight gradient: K = tokens, sliced
+    probe = B.gemm_op(x, dy, nan_like((8,), torch.float32), k, n, tokens, ta=True)
+    tile, slices = B.lithos_gemm_split_hint(probe, 256)
+    assert tile == 256 and slices == 5
+    outs = []
+    for atom_blocks in (0, 64):
+        planes = nan_like((slices, k, n), torch.float32)
+        dw = nan_like((k, n), torch.bfloat16)
+        launch(B.gemm_op(x, dy, planes, k, n, tokens, ta=True, tile=tile, k_slices=slices), atom_blocks)
+        launch(B.sum_slices_op(planes, dw, k, n, slices), atom_blocks * 8)
+        outs.append(dw)
+    assert bits_equal(outs[0], outs[1])
+    rows = np.sort(rng.choice(k, 64, replace=False))
+    ref = O.gemm(np.ascontiguousarray(x_bits[:, rows]), dy_bits, ta=True)
+    # sums of 16384 products of N(0,1) values: |dW| ~ 128, fp32 accumulation error ~ 2^-22 * K * |terms|
+    bf16_close(outs[0][torch.from_numpy(rows).cuda()], ref, abs_tol=2.0 ** -22 * tokens * 4)
