@@ -99,7 +99,7 @@ struct TileStage {
 // per CU), 128x128 tiles three workgroups and 64x64 tiles four: left alone, the compiler spends
 // the whole register file on hoisted epilogue addresses and halves the occupancy.
 template <int BM, int BN, int WGM, int WGN, bool TA, bool TB, bool SPLIT, bool ST>
-__global__ __launch_bounds__(WGM * WGN * 64, BM >= 256 ? 2 : BM >= 128 ? (SPLIT ? 2 : 3) : 4)
+__global__ __launch_bounds__(WGM * WGN * 64, BM >= 256 ? 2 : BM >= 128 ? 3 : 4)
 void gemm_tile_kernel(GemmArgs g, AtomArgs atom)
 {
     constexpr int T = WGM * WGN * 64, BK = 64;
