@@ -93,8 +93,8 @@ def wl_cfg2(args, B, inputs, torch):
                           "8192 rows of one 8192^3 best-effort GEMM" % rows,
                 "be_gemm_tflops": 2.0 * rows * 8192 * 8192 / be_s * 1e-12}
 
-    return dict(name="cfg2: HP 6-layer MLP batch 8 hidden 4096 Poisson 200 req/s on 64 CUs + BE bf16 8192^3 GEMMs "
-                     "on 192 CUs, idle-CU stealing, atomized",
+    return dict(name="cfg2: HP 6-layer MLP batch 8 hidden 4096 Poisson 200 req/s on %d CUs + BE bf16 8192^3 GEMMs "
+                     "on %d CUs, idle-CU stealing, atomized" % (HP_CUS, 256 - HP_CUS),
                 hp_requests=[chain.ops(x) for x in pool], rate=200.0, be=be, cpu_baseline=cpu_baseline, keep=[chain, pool])
 
 
@@ -119,8 +119,8 @@ def wl_cfg3(args, B, inputs, torch):
         return {"value": (time.perf_counter() - t0) * 1e3, "unit": "ms", "cores": O.num_threads(), "kind": "oracle",
                 "sample": "1 high-priority request at batch 1 (12 layers, 128 tokens)"}
 
-    return dict(name="cfg3: HP 12-layer encoder hidden 768 12 heads seq 128 batch %d, Poisson at 80%% of its 64-CU "
-                     "service rate + BE training-shaped GEMMs (24 layers, hidden 1024, FFN 4096, 16384 tokens)" % b,
+    return dict(name="cfg3: HP 12-layer encoder hidden 768 12 heads seq 128 batch %d, Poisson at 80%% of its %d-CU "
+                     "service rate + BE training-shaped GEMMs (24 layers, hidden 1024, FFN 4096, 16384 tokens)" % (b, HP_CUS),
                 hp_requests=[chain.ops()], rate=None, be=be, cpu_baseline=cpu_baseline, keep=[chain, keep],
                 distinct=distinct, chain=chain)
 
@@ -145,7 +145,7 @@ def wl_cfg5(args, B, inputs, torch):
                 "sample": "1 decoder layer at batch 1, scaled by %d layers" % n_layers}
 
     return dict(name="cfg5: HP %d-layer decoder decode step hidden 4096 GQA 32/8 FFN 14336 KV 2048 batch %d, Poisson at "
-                     "80%% of its 64-CU service rate + BE bf16 8192^3 GEMMs" % (n_layers, b),
+                     "80%% of its %d-CU service rate + BE bf16 8192^3 GEMMs" % (n_layers, b, HP_CUS),
                 hp_requests=[chain.ops()], rate=None, be=be, cpu_baseline=cpu_baseline, keep=[chain])
 
 
@@ -153,12 +153,15 @@ def wl_cfg5(args, B, inputs, torch):
 # stacking legs
 # ---------------------------------------------------------------------------------------------
 
+HP_CUS = 64      # high-priority quota; the best-effort tenant owns the other 256 - HP_CUS (set by --hp-cus)
+
+
 def make_world(B, cfg, masks=True):
     ctx = B.lithos_init(0, cfg)
     if not masks:
         return ctx, [], B.lithos_tenant_create(ctx, B.CLASS_HP, None), B.lithos_tenant_create(ctx, B.CLASS_BE, None)
-    p_hp = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 64, B.MASK_STRIPED, 0))
-    p_be = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 192, B.MASK_STRIPED, 64))
+    p_hp = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, HP_CUS, B.MASK_STRIPED, 0))
+    p_be = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 256 - HP_CUS, B.MASK_STRIPED, HP_CUS))
     return ctx, [p_hp, p_be], B.lithos_tenant_create(ctx, B.CLASS_HP, p_hp), B.lithos_tenant_create(ctx, B.CLASS_BE, p_be)
 
 
@@ -203,9 +206,15 @@ def main():
     ap.add_argument("--atom-us", type=float, default=250.0)
     ap.add_argument("--max-outstanding", type=int, default=1)
     ap.add_argument("--be-tile", type=int, default=256)
+    ap.add_argument("--hp-cus", type=int, default=64, help="high-priority quota in CUs (multiple of 8, 8..248); best effort owns the rest")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     args = ap.parse_args()
+    global HP_CUS
+    if args.hp_cus % 8 or not 8 <= args.hp_cus <= 248:
+        print("bench.py: --hp-cus must be a multiple of 8 between 8 and 248", file=sys.stderr)
+        sys.exit(2)
+    HP_CUS = args.hp_cus
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -230,7 +239,7 @@ def main():
         return B.Config.default(atom_duration_us=args.atom_us, max_outstanding=args.max_outstanding,
                                 max_outstanding_hp=64, steal=steal, atomize=atomize)
 
-    # offered load: fixed for cfg2; else 80 % of the solo service rate on the 64-CU quota (Section 7.1 rule)
+    # offered load: fixed for cfg2; else 80 % of the solo service rate on the high-priority quota (Section 7.1 rule)
     rate = wl["rate"]
     if rate is None:
         ctx, parts, t_hp, t_be = make_world(B, sched_cfg(0, 0))
@@ -330,7 +339,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl["name"], "offered_load_per_s": rate, "atom_duration_us": args.atom_us,
-                   "max_outstanding": args.max_outstanding, "be_gemm_tile": args.be_tile, "cu_split": "64/192"},
+                   "max_outstanding": args.max_outstanding, "be_gemm_tile": args.be_tile, "cu_split": "%d/%d" % (HP_CUS, 256 - HP_CUS)},
         "hp_p50_ms": main_sum["p50_us"] * 1e-3,
         "hp_p99_ms": main_sum["p99_us"] * 1e-3,
         "hp_p99_over_ideal": (main_sum["p99_us"] / ideal) if ideal else None,
