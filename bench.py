@@ -536,6 +536,64 @@ def rightsize_sweep(args, B, inputs, torch):
         cu_time += count * r.chosen_us * r.chosen_cus
         full_cs += count * 256 * r.full_us
         chosen_cs += count * r.chosen_cus * r.chosen_us
+
+    # measured end-to-end: the high-priority request and one best-effort pass with every kernel on its chosen
+    # CU count against the same launches on all 256 CUs (kernels on different CU-masked queues are ordered
+    # through a stream of the caller's, in both runs alike; it must not be the null stream, which the
+    # library reads as "no ordering stream")
+    chosen = {k["kernel"]: k["chosen_cus"] for k in rows}
+    parts = {c: B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, c, B.MASK_STRIPED, 0)) for c in set(chosen.values()) | {256}}
+    order = torch.cuda.Stream()
+    stream = order.cuda_stream
+    hp_ops = wl["hp_requests"][0]
+    hp_names = list(kernels)[:7]
+    hp_cus = [256, 256] + [chosen[hp_names[(i - 2) % 7]] for i in range(2, len(hp_ops))]
+    be_ops = wl["be"]["ops"]
+    be_names = list(wl["distinct"])
+    be_cus = [chosen[be_names[j % len(be_names)]] for j in range(len(be_ops))]
+
+    def chain_ms(ops, cus, reps):
+        t = []
+        for _ in range(reps + 2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for op, c in zip(ops, cus):
+                B.lithos_launch_atomized(ctx, op, (0, 0, 0), 0, parts[c], stream)
+            torch.cuda.synchronize()
+            t.append((time.perf_counter() - t0) * 1e3)
+        return float(np.median(t[2:]))
+    measured = {}
+    for name, ops, cus, reps in (("hp_request", hp_ops, hp_cus, 30), ("be_pass", be_ops, be_cus, 6)):
+        full_ms = chain_ms(ops, [256] * len(ops), reps)
+        sized_ms = chain_ms(ops, cus, reps)
+        measured[name] = {"full_gpu_ms": full_ms, "right_sized_ms": sized_ms, "slowdown": sized_ms / full_ms - 1.0,
+                          "mean_cus": float(np.mean(cus))}
+    # the same rule applied to a whole chain on ONE queue (what a tenant's quota is): smallest CU count whose
+    # chain latency stays within the slip of the full GPU's
+    def chain_on(ops, part, reps):
+        t = []
+        for _ in range(reps + 2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for op in ops:
+                B.lithos_launch_atomized(ctx, op, (0, 0, 0), 0, part, None)
+            B.lithos_partition_sync(ctx, part)
+            t.append((time.perf_counter() - t0) * 1e3)
+        return float(np.median(t[2:]))
+    for c in [c for c in parts if c != 256]:         # few live queues: dozens of them slow every dispatch down
+        B.lithos_destroy_partition(parts.pop(c))
+    per_chain = {}
+    for name, ops, reps in (("hp_request", hp_ops, 10), ("be_pass", be_ops, 3)):
+        curve = {256: chain_on(ops, parts[256], reps)}
+        for c in range(8, 256, 8):
+            part = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, c, B.MASK_STRIPED, 0))
+            curve[c] = chain_on(ops, part, reps)
+            B.lithos_destroy_partition(part)
+        best = min(c for c in curve if curve[c] <= 1.04 * curve[256])
+        per_chain[name] = {"chosen_cus": best, "full_gpu_ms": curve[256], "chosen_ms": curve[best],
+                           "slowdown": curve[best] / curve[256] - 1.0, "curve_ms": [round(curve[c], 3) for c in sorted(curve)]}
+    for p in parts.values():
+        B.lithos_destroy_partition(p)
     B.lithos_shutdown(ctx)
     out = {"metric": "right-sizing sweep (cfg4): CU-seconds saved and end-to-end slowdown at 4 % per-kernel slip",
            "value": 1.0 - (cu_time / t_chosen) / 256.0, "unit": "fraction of CUs saved (time-weighted)",
@@ -544,6 +602,10 @@ def rightsize_sweep(args, B, inputs, torch):
                                   "5 warm + 50 timed launches, median" % args.batch, "slowdown": 0.04},
            "cu_seconds_saved_per_pass": (full_cs - chosen_cs) * 1e-6,
            "predicted_end_to_end_slowdown": t_chosen / t_full - 1.0,
+           "measured_end_to_end_per_kernel_masks": measured,
+           "measured_end_to_end_note": "kernels on different CU-masked queues are chained by events through the caller's stream "
+                                       "(a queue's CU mask is fixed at creation); full_gpu_ms uses the same chaining on one queue",
+           "measured_per_chain_mask": per_chain,
            "time_weighted_model_r2": sum(k["model_r2"] * k["launches_per_pass"] * k["full_us"] for k in rows) / t_full,
            "kernels": rows,
            "paper_context": "LithOS on A100: capacity savings up to 51 %, mean 26 %, at latency slip 1.1; R^2 0.92-0.99"}
