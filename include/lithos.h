@@ -219,7 +219,12 @@ int lithos_gemm_split_hint(const lithos_op_t* op, int32_t n_cus, int32_t* tile_o
  * grid {0,0,0} = use lithos_op_grid's; otherwise it must have the same total.
  * part NULL = an unmasked queue.  stream (hipStream_t, may be NULL = none):
  * the first atom waits for work already queued on it and it waits for the
- * last atom, so the caller's own stream work orders with the launch.
+ * last atom, so the caller's own stream work orders with the launch, and
+ * launches on different partitions that name the same stream run in call
+ * order.  NULL is "no ordering stream", not the legacy default stream: work
+ * on the default stream (torch's default) has to be drained by the caller,
+ * or moved to a created stream whose handle is passed here.  Every such hop
+ * between queues costs an event round trip (tens of microseconds).
  * Returns after enqueueing; errors in shape/alignment are reported before
  * anything is launched. */
 int lithos_launch_atomized(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3 grid,

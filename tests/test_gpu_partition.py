@@ -120,3 +120,31 @@ def test_prelude_form_of_algorithm_1_gives_the_same_bits():
     for key in ((64,), (256,), (128,), ("mlp",)):
         assert bits_equal(outs[(0,) + key], outs[(1,) + key])
     assert rel_fro(outs[(1, 256)], O.gemm(a_bits, b_bits)) <= 1e-4
+
+
+def test_ordering_stream_chains_launches_on_different_partitions():
+    """Kernels of one chain launched on queues with different CU masks, ordered through a stream of the
+    caller's: same bits as the chain on one queue, and the caller's own work on that stream runs after."""
+    from paper_2504_15465_amd.models import MlpChain, run_ops
+    c = ctx()
+    parts = [B.lithos_create_partition(c, B.lithos_make_mask(c, n, B.MASK_STRIPED, first)) for n, first in ((64, 0), (128, 64), (32, 192))]
+    try:
+        chain = MlpChain(inputs.mlp_params(4, 1024, seed=1), 8)
+        chain.set_input(inputs.mlp_requests(pool=1, batch=8, hidden=1024, seed=2)[0])
+        ops = chain.ops()
+        run_ops(c, ops, parts[0])
+        ref = chain.out.clone()
+        order = torch.cuda.Stream()
+        assert order.cuda_stream != 0
+        for rep in range(5):
+            chain.out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            for i, op in enumerate(ops):
+                B.lithos_launch_atomized(c, op, (0, 0, 0), 2 if i % 3 == 0 else 0, parts[i % 3], order.cuda_stream)
+            with torch.cuda.stream(order):
+                snap = chain.out.clone()          # the caller's own work on the ordering stream
+            order.synchronize()
+            assert bits_equal(snap, ref), "repetition %d" % rep
+    finally:
+        for p in parts:
+            B.lithos_destroy_partition(p)
