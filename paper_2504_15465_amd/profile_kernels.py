@@ -20,7 +20,7 @@ from .models import DecoderChain, EncoderChain, MlpChain, training_block_ops
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "mlp", "skinny", "encoder", "decoder", "train"])
+    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "mlp", "skinny", "encoder", "decoder", "train", "atom_sweep"])
     ap.add_argument("--tile", type=int, default=256)
     ap.add_argument("--batch", type=int, default=4)
     ap.add_argument("--layers", type=int, default=4)
@@ -63,6 +63,36 @@ def main():
             for o in ops:
                 B.lithos_launch_atomized(ctx, o, (0, 0, 0), 0, part, None)
         B.lithos_partition_sync(ctx, part)
+    elif args.what == "atom_sweep":
+        # Atom overhead against atom size (device time stamps on the launch's own queue, whole and atomized
+        # launches alternating): the 8192^3 GEMM on all CUs, and configuration 1 (512^3, 64x64 tiles, 32 CUs).
+        def sweep(title, op, p, sizes, reps):
+            grid, wg = B.lithos_op_grid(ctx, op)
+            total = grid[0] * grid[1] * grid[2]
+            print("## %s: %d blocks, %d resident per CU" % (title, total, wg))
+            print("| atom_blocks | atoms | whole us | atomized us | overhead % |\n|---|---|---|---|---|")
+            B.lithos_time_launch(ctx, op, 0, p, 3, 3)
+            for ab in sizes:
+                rounds = [(B.lithos_time_launch(ctx, op, 0, p, 1, reps)[1], B.lithos_time_launch(ctx, op, ab, p, 1, reps)[1])
+                          for _ in range(4)]
+                w = sorted(r[0] for r in rounds)[2]
+                a = sorted(r[1] for r in rounds)[2]
+                print("| %d | %d | %.1f | %.1f | %+.1f |" % (ab, -(-total // ab), w, a, (a / w - 1) * 100), flush=True)
+        n = 8192
+        a_bits, b_bits = inputs.gemm_operands(n, n, n, seed=4)
+        a, b = inputs.bits_to_torch(a_bits, "cuda"), inputs.bits_to_torch(b_bits, "cuda")
+        c = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
+        torch.cuda.synchronize()
+        sweep("8192^3 bf16 GEMM, 256x256 tiles, %d CUs" % args.cus, B.gemm_op(a, b, c, n, n, n, tile=256), part,
+              (512, 256, 128, 64, 32), 5)
+        a_bits, b_bits = inputs.gemm_operands(512, 512, 512, seed=0)
+        a, b = inputs.bits_to_torch(a_bits, "cuda"), inputs.bits_to_torch(b_bits, "cuda")
+        c32 = torch.empty((512, 512), dtype=torch.float32, device="cuda")
+        p32 = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 32))
+        torch.cuda.synchronize()
+        sweep("configuration 1: 512^3 bf16 GEMM, 64x64 tiles, 32 CUs", B.gemm_op(a, b, c32, 512, 512, 512, tile=64), p32,
+              (32, 16, 8, 4), 20)
+        B.lithos_destroy_partition(p32)
     elif args.what == "train":          # fwd, dX, dW GEMMs of --layers transformer blocks (hidden 1024, FFN 4096, 16384 tokens)
         ops, _, keep, _ = training_block_ops(n_layers=args.layers, split_cus=args.cus)
         torch.cuda.synchronize()
