@@ -398,3 +398,23 @@ def test_training_shapes_full_size_sampled_rows():
     ref = O.gemm(np.ascontiguousarray(x_bits[:, rows]), dy_bits, ta=True)
     # sums of 16384 products of N(0,1) values: |dW| ~ 128, fp32 accumulation error ~ 2^-22 * K * |terms|
     bf16_close(outs[0][torch.from_numpy(rows).cuda()], ref, abs_tol=2.0 ** -22 * tokens * 4)
+
+
+@pytest.mark.parametrize("tile,k", [(128, 320), (256, 320), (256, 264)])
+def test_split_bf16_output_of_plain_bf16_gemm(tile, k):
+    """C written as a hi + lo bf16 pair by the kernels that take ordinary bf16 operands (full tiles through
+    LDS in two passes where the kernel has that path, ragged tiles element by element): the hi plane is the
+    single-plane result bit for bit, hi + lo carries ~16 significant bits."""
+    m, n = 520, 776
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=61)
+    ref = O.gemm(a_bits, b_bits)
+    a, b = dev_bits(a_bits), dev_bits(b_bits)
+    single = nan_like((m, n), torch.bfloat16)
+    pair = nan_like((2, m, n), torch.bfloat16)
+    torch.cuda.synchronize()
+    B.lithos_launch_atomized(ctx(), B.gemm_op(a, b, single, m, n, k, tile=tile))
+    B.lithos_launch_atomized(ctx(), B.gemm_op(a, b, pair, m, n, k, tile=tile, c_split=True), (0, 0, 0), 2)
+    B.lithos_partition_sync(ctx(), None)
+    assert bits_equal(pair[0], single)
+    got = pair[0].cpu().to(torch.float64).numpy() + pair[1].cpu().to(torch.float64).numpy()
+    assert np.abs(got - ref).max() <= 2.0 ** -15 * np.abs(ref).max() + 2.0 ** -22 * k
