@@ -2,10 +2,10 @@
 // This file validates a GEMM descriptor, picks the kernel and launches one atom.
 //
 // Kernel families (one translation unit each):
-//  * gemm_lds256_kernel (gemm_lds256.hip) - 256x256 tiles, K % 64 == 0, any operand
+//  * gemm_lds256_kernel (gemm_lds256.hpp, gemm_lds256_{wide,elem}.hip) - 256x256 tiles, K % 64 == 0, any operand
 //    layout: global memory straight into LDS, k-strided operands read with the
 //    transposing LDS load; the best-effort and training-shaped GEMMs;
-//  * gemm_tile_kernel (gemm_tile.hpp, gemm_tile{64,128,256}.hip) - 64/128/256
+//  * gemm_tile_kernel (gemm_tile.hpp, gemm_tile{64,128}.hip, gemm_tile256_{wide,elem}.hip) - 64/128/256
 //    tiles through registers, ragged K, split-bf16 A;
 //  * gemm_skinny_*_kernel (gemm_skinny.hip) - M <= 32 rows (bf16 or fp32
 //    activations) against a [N,K] bf16 weight matrix: HBM-bound, the weights are
@@ -39,10 +39,10 @@ static bool staged_epilogue(const lithos_op_t& op)
 static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split, bool st)
 {
     switch (variant) {
-    case V_LDS256: return gemm_lds256_fn(ta, tb, st);
+    case V_LDS256: return st ? gemm_lds256_wide_fn(ta, tb) : gemm_lds256_elem_fn(ta, tb);
     case V_TILE64: return gemm_tile64_fn(ta, tb, split, st);
     case V_TILE128: return gemm_tile128_fn(ta, tb, split, st);
-    case V_TILE256: return gemm_tile256_fn(ta, tb, st);
+    case V_TILE256: return st ? gemm_tile256_wide_fn(ta, tb) : gemm_tile256_elem_fn(ta, tb);
     default: return gemm_skinny_fn(variant, a32);
     }
 }

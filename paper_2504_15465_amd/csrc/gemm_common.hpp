@@ -209,8 +209,10 @@ typedef void (*gemm_fn)(GemmArgs, AtomArgs);
 // kernel tables, one translation unit per family
 gemm_fn gemm_tile64_fn(bool ta, bool tb, bool split, bool st);
 gemm_fn gemm_tile128_fn(bool ta, bool tb, bool split, bool st);
-gemm_fn gemm_tile256_fn(bool ta, bool tb, bool st);
-gemm_fn gemm_lds256_fn(bool ta, bool tb, bool st);
+gemm_fn gemm_tile256_wide_fn(bool ta, bool tb);
+gemm_fn gemm_tile256_elem_fn(bool ta, bool tb);
+gemm_fn gemm_lds256_wide_fn(bool ta, bool tb);
+gemm_fn gemm_lds256_elem_fn(bool ta, bool tb);
 gemm_fn gemm_skinny_fn(int variant, bool a32);
 
 constexpr int SKINNY_WAVES = 8;     // wavefronts per workgroup of the skinny kernels, each owning one slice of K

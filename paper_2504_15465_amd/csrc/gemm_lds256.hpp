@@ -1,3 +1,4 @@
+#pragma once
 #include "gemm_common.hpp"
 
 namespace lithos {
@@ -215,13 +216,8 @@ void gemm_lds256_kernel(GemmArgs g, AtomArgs atom)
     });
 }
 
-gemm_fn gemm_lds256_fn(bool ta, bool tb, bool st)
-{
-#define PICK(ST)                                                                                       \
+#define LITHOS_LDS256_PICK(ST)                                                                                              \
     (ta ? (tb ? (gemm_fn)gemm_lds256_kernel<2, 4, ST, true, false> : (gemm_fn)gemm_lds256_kernel<2, 4, ST, true, true>)    \
         : (tb ? (gemm_fn)gemm_lds256_kernel<2, 4, ST, false, false> : (gemm_fn)gemm_lds256_kernel<2, 4, ST, false, true>))
-    return st ? PICK(true) : PICK(false);
-#undef PICK
-}
 
 } // namespace lithos
