@@ -42,9 +42,33 @@ if ROOT not in sys.path:
 METRIC = "high-priority p99 latency + aggregate tput under 2-tenant stacking; atom overhead %"
 MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per whole 8192^3 launch of the 256x256-tile GEMM, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# scaled by the 1 GiB copy calibration (profiles/): filled in by measurement, None until measured.
+# HBM bytes per whole 8192^3 launch, by GEMM tile: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per dispatch),
+# each scaled by what the same counter reads for a 1 GiB device-to-device copy (fetch x 2.00, write x 1.00).
+# Source: profiles/gemm_lds256_8192_and_cfg2_stacking.md, section 3 (256 tiles: 786859 KiB x 2 + 131072 KiB).
 TRAFFIC_BYTES = {256: 1.75e9, 128: 3.36e9}
+ALGORITHMIC_BYTES_8192 = 3 * 8192 * 8192 * 2.0      # A and B read once, C written once, bf16
+TAIL_REQUESTS, TAIL_WARMUP = 2000, 100              # fixed-size legs behind "tail_study" (p99 needs samples)
+
+
+def plan_legs(steps, warmup, comparator_cap=1000, comparator_warm_cap=100):
+    """How many requests each leg of a stacking run offers: (untimed, timed) per leg.
+
+    The headline leg times exactly `steps` requests after `warmup`; the comparator legs
+    (same arrival process, their own draw) are capped so that long runs do not repeat
+    every leg at full length.  Every leg has at least one timed request."""
+    k, w = max(1, int(steps)), max(0, int(warmup))
+    return {"main": (w, k), "comparator": (min(w, comparator_warm_cap), min(k, comparator_cap)),
+            "tail": (TAIL_WARMUP, TAIL_REQUESTS)}
+
+
+def split_arrivals(arrivals, warm):
+    """(untimed arrivals, timed arrivals re-based to start after the last untimed one)."""
+    n = len(arrivals)
+    if n < 1:
+        raise ValueError("a leg needs at least one request")
+    warm = max(0, min(int(warm), n - 1))
+    base = arrivals[warm - 1] if warm > 0 else 0.0
+    return arrivals[:warm], arrivals[warm:] - base
 
 
 def nearest_rank(x, q):
@@ -179,9 +203,9 @@ def stacked_leg(B, torch, wl, t_hp, t_be, arrivals, warm):
     drv = B.lithos_drive_closed_loop_start(t_be, wl["be"]["ops"], depth=2) if t_be is not None else None
     if drv is not None:
         time.sleep(0.2)
-    if warm > 0:
-        B.lithos_drive_open_loop(t_hp, wl["hp_requests"], arrivals[:warm])
-    arr = arrivals[warm:] - (arrivals[warm - 1] if warm > 0 else 0.0)
+    warm_arr, arr = split_arrivals(arrivals, warm)
+    if len(warm_arr) > 0:
+        B.lithos_drive_open_loop(t_hp, wl["hp_requests"], warm_arr)
     s0 = B.lithos_tenant_stats(t_be) if t_be is not None else None
     torch.cuda.synchronize() if drv is None else None
     t0 = time.perf_counter()
@@ -209,6 +233,7 @@ def main():
     ap.add_argument("--hp-cus", type=int, default=64, help="high-priority quota in CUs (multiple of 8, 8..248); best effort owns the rest")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
+    ap.add_argument("--no-tail-study", action="store_true", help="skip the fixed-size legs (2000 requests each) behind tail_study")
     args = ap.parse_args()
     global HP_CUS
     if args.hp_cus % 8 or not 8 <= args.hp_cus <= 248:
@@ -253,40 +278,61 @@ def main():
             solo = (time.perf_counter() - t0) / 10
         drop_world(B, ctx, parts, [t_hp, t_be])
         rate = 0.8 / solo
-    arrivals = inputs.poisson_arrivals(rate, W + K, seed=3)
+    legs = plan_legs(K, W)
 
-    def summarise(r, skip=0):
-        lat = r["lat"][skip:]
-        return {"p50_us": nearest_rank(lat, 0.5), "p99_us": nearest_rank(lat, 0.99),
+    def summarise(r):
+        lat = r["lat"]
+        return {"p50_us": nearest_rank(lat, 0.5), "p99_us": nearest_rank(lat, 0.99), "requests": int(len(lat)),
                 "be_tflops": r["be_iters"] * wl["be"]["flop"] / r["be_secs"] * 1e-12}
 
-    comp = {}
-    if not args.no_comparators:
-        n_c = min(K, 1000) + 100
-        arr_c = arrivals[:n_c]
-        # (i) high-priority alone on the whole GPU ("ideal"), (ii) best-effort alone
+    def comparators(warm, timed, seed):
+        """(i) high-priority alone on the whole GPU ("ideal"), (ii) best-effort alone, (iii) unpartitioned
+        co-execution (two plain queues, no masks, no atoms), (iv) static masks, (v) masks + stealing without
+        atoms; every leg draws `warm + timed` arrivals of the same process."""
+        arr = inputs.poisson_arrivals(rate, warm + timed, seed=seed)
+        out = {}
         ctx, parts, t_hp, t_be = make_world(B, None, masks=False)
-        r = stacked_leg(B, torch, wl, t_hp, None, arr_c, 100)
-        comp["hp_alone_full_gpu"] = {k: v for k, v in summarise(r).items() if k != "be_tflops"}
+        r = stacked_leg(B, torch, wl, t_hp, None, arr, warm)
+        out["hp_alone_full_gpu"] = {k: v for k, v in summarise(r).items() if k != "be_tflops"}
         drv = B.lithos_drive_closed_loop_start(t_be, wl["be"]["ops"], depth=2)
         time.sleep(2.0)
         iters, secs = B.lithos_drive_closed_loop_stop(drv)
-        comp["be_alone_full_gpu"] = {"iterations_per_s": iters / secs, "tflops": iters * wl["be"]["flop"] / secs * 1e-12}
-        # (iii) unpartitioned co-execution: two plain queues, no masks, no atoms
-        comp["unpartitioned_coexecution"] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr_c, 100))
+        out["be_alone_full_gpu"] = {"iterations_per_s": iters / secs, "tflops": iters * wl["be"]["flop"] / secs * 1e-12}
+        out["unpartitioned_coexecution"] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr, warm))
         drop_world(B, ctx, parts, [t_hp, t_be])
-        # (iv) static masks, (v) masks + stealing, both without atoms
         for name, steal in (("static_masks", 0), ("masks_stealing", 1)):
             ctx, parts, t_hp, t_be = make_world(B, sched_cfg(steal, 0))
-            comp[name] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr_c, 100))
+            out[name] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr, warm))
             drop_world(B, ctx, parts, [t_hp, t_be])
+        return out
 
-    # ---- main leg: quotas 64/192, stealing, atomization --------------------------------------------
+    comp = {} if args.no_comparators else comparators(*legs["comparator"], seed=3)
+
+    # ---- main leg: quotas, stealing, atomization: exactly K timed steps after W warm-up ---------------
+    arrivals = inputs.poisson_arrivals(rate, W + K, seed=3)
     ctx, parts, t_hp, t_be = make_world(B, sched_cfg(1, 1))
-    r = stacked_leg(B, torch, wl, t_hp, t_be, arrivals, W)          # exactly K timed steps after W warm-up
+    r = stacked_leg(B, torch, wl, t_hp, t_be, arrivals, W)
     s_hp = B.lithos_tenant_stats(t_hp)
     s0, s1 = r["s0"], r["s1"]
     main_sum = summarise(r)
+
+    # ---- tail study: the same ladder on legs of a fixed size, so that p99 is a percentile and not the
+    # maximum of a handful of requests (the headline keeps to --steps) -----------------------------------
+    tail = None
+    if not args.no_tail_study:
+        tw, tn = legs["tail"]
+        tail = {} if args.no_comparators else comparators(tw, tn, seed=6)
+        st0 = B.lithos_tenant_stats(t_be)
+        rt = stacked_leg(B, torch, wl, t_hp, t_be, inputs.poisson_arrivals(rate, tw + tn, seed=6), tw)
+        tail["full_scheduler"] = summarise(rt)
+        tail["full_scheduler"]["be_revocations"] = int(rt["s1"].revocations - rt["s0"].revocations)
+        tail["full_scheduler"]["be_stolen_atoms"] = int(rt["s1"].stolen_atoms - rt["s0"].stolen_atoms)
+        tail["requests_per_leg"], tail["warmup_per_leg"] = tn, tw
+        if "static_masks" in tail:
+            tail["hp_p99_over_static_masks"] = tail["full_scheduler"]["p99_us"] / tail["static_masks"]["p99_us"]
+            tail["be_tflops_over_alone"] = tail["full_scheduler"]["be_tflops"] / tail["be_alone_full_gpu"]["tflops"]
+            tail["hp_p99_vs_unpartitioned"] = tail["unpartitioned_coexecution"]["p99_us"] / tail["full_scheduler"]["p99_us"]
+    ctx_stats = B.lithos_stats(ctx)
 
     # ---- atom overhead and roofline of the dominant kernel (device time stamps on its queue) -------
     p_all = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 256, B.MASK_STRIPED, 0))
@@ -302,6 +348,7 @@ def main():
     rounds = [(B.lithos_time_launch(ctx, op, 0, p_all, 1, 5), B.lithos_time_launch(ctx, op, atom_blocks, p_all, 1, 5))
               for _ in range(8)]
     whole_mean = float(np.mean([w[0] for w, _ in rounds]))
+    n_roof = 5 * len(rounds)
     whole_med = float(np.median([w[1] for w, _ in rounds]))
     at_med = float(np.median([a[1] for _, a in rounds]))
     overhead_pct = (at_med - whole_med) / whole_med * 100.0
@@ -342,6 +389,8 @@ def main():
                    "max_outstanding": args.max_outstanding, "be_gemm_tile": args.be_tile, "cu_split": "%d/%d" % (HP_CUS, 256 - HP_CUS)},
         "hp_p50_ms": main_sum["p50_us"] * 1e-3,
         "hp_p99_ms": main_sum["p99_us"] * 1e-3,
+        "p99_samples": K,
+        "p99_note": "nearest rank over exactly --steps requests; below 100 samples it is their maximum, see tail_study",
         "hp_p99_over_ideal": (main_sum["p99_us"] / ideal) if ideal else None,
         "hp_p99_vs_unpartitioned": (comp["unpartitioned_coexecution"]["p99_us"] / main_sum["p99_us"]) if comp else None,
         "hp_served_per_s": hp_served,
@@ -353,12 +402,18 @@ def main():
                                  "prelude_form_overhead_pct": prelude_pct},
         "scheduler": {"be_atoms": int(s1.atoms - s0.atoms), "be_kernels": int(s1.kernels - s0.kernels),
                       "be_stolen_atoms": int(s1.stolen_atoms - s0.stolen_atoms),
+                      "be_revocations": int(s1.revocations - s0.revocations),
+                      "context_totals": {"kernels": int(ctx_stats.kernels), "atoms": int(ctx_stats.atoms),
+                                         "steals": int(ctx_stats.stolen_atoms), "revocations": int(ctx_stats.revocations),
+                                         "mispredicts": int(ctx_stats.mispredicts)},
                       "be_mispredict_rate": (s1.mispredicts / s1.predictions) if s1.predictions else None,
                       "hp_mispredict_rate": (s_hp.mispredicts / s_hp.predictions) if s_hp.predictions else None},
         "comparators": comp,
+        "tail_study": tail,
         "roofline": {"bound": "mfma", "kernel": desc, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
-                     "launch_us": whole_mean, "flop_per_launch": flop},
+                     "traffic_over_algorithmic": (traffic / ALGORITHMIC_BYTES_8192) if traffic else None,
+                     "launch_us": whole_mean, "launches_timed": n_roof, "flop_per_launch": flop},
         "cpu_baseline": cpu,
         "paper_context": "LithOS on A100 (its NVIDIA hardware): 13x lower P99 than MPS, 3x lower tail and 1.6x "
                          "aggregate throughput vs best prior system; atomization cost 10% BE throughput",

@@ -216,7 +216,10 @@ int lithos_gemm_split_hint(const lithos_op_t* op, int32_t n_cus, int32_t* tile_o
 /* Run `op` as ceil(total/atom_blocks) launches, atom i covering logical
  * blocks [i*atom_blocks, min((i+1)*atom_blocks, total)) of the grid numbered
  * idx = z*gy*gx + y*gx + x.  atom_blocks == 0 or >= total: one launch.
- * grid {0,0,0} = use lithos_op_grid's; otherwise it must have the same total.
+ * grid {0,0,0} = use lithos_op_grid's; otherwise it must have the same total
+ * (else LITHOS_EINVAL).  Atoms are ranges of the linear index, which every
+ * factorisation of that total numbers alike, so a caller's grid only has to
+ * agree in its total: the operator keeps its own tile geometry.
  * part NULL = an unmasked queue.  stream (hipStream_t, may be NULL = none):
  * the first atom waits for work already queued on it and it waits for the
  * last atom, so the caller's own stream work orders with the launch, and
@@ -226,7 +229,9 @@ int lithos_gemm_split_hint(const lithos_op_t* op, int32_t n_cus, int32_t* tile_o
  * or moved to a created stream whose handle is passed here.  Every such hop
  * between queues costs an event round trip (tens of microseconds).
  * Returns after enqueueing; errors in shape/alignment are reported before
- * anything is launched. */
+ * anything is launched.  If a launch fails after some atoms were enqueued,
+ * the ordering stream is still made to wait for those.  Thread-safe: calls
+ * on one context are serialised inside the library. */
 int lithos_launch_atomized(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3 grid,
                            uint32_t atom_blocks, const lithos_partition_t* part, void* stream);
 
@@ -277,7 +282,12 @@ int lithos_time_launch(lithos_ctx_t* ctx, const lithos_op_t* op, uint32_t atom_b
 typedef struct lithos_stats {
     uint64_t kernels;        /* kernels dispatched */
     uint64_t atoms;          /* atoms launched */
-    uint64_t stolen_atoms;   /* atoms launched on a mask wider than the tenant's quota */
+    uint64_t stolen_atoms;   /* "steals": atoms launched on a mask wider than the tenant's quota (Section 4.3
+                                'TPC Stealing') */
+    uint64_t revocations;    /* atom boundaries at which a kernel's next atom lost CUs that its previous atom
+                                had borrowed, because their owner has work again or their timers are not free
+                                (Section 4.4 'Operation', second paragraph: stealing stops for the thief's
+                                later atoms; atoms in flight run to completion) */
     uint64_t predictions;    /* atoms launched with a prediction */
     uint64_t mispredicts;    /* |predicted - measured| > 50 us (Section 7.4) */
     double   abs_err_sum_us;
@@ -303,6 +313,9 @@ int lithos_sync_mark(lithos_tenant_t* t);
 int lithos_sync(lithos_tenant_t* t);
 int lithos_poll(lithos_tenant_t* t, uint64_t ticket, int* done_out);
 int lithos_tenant_stats(lithos_tenant_t* t, lithos_stats_t* out);
+/* Totals over every tenant the context has had (destroyed ones included): kernels, atoms launched,
+ * steals, revocations, predictions and mispredictions. */
+int lithos_stats(lithos_ctx_t* ctx, lithos_stats_t* out);
 
 /* ---- load generators (native, so that two tenants do not share an interpreter lock) */
 /* These stand in for the paper's clients (Section 7.1: high-priority

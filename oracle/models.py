@@ -46,29 +46,43 @@ def mlp_forward(x_bits, layers, eps: float = 1e-5):
 
 # -------------------------------------------------------------- encoder ----
 
-def encoder_forward(x32, layers, batch: int, seq: int, heads: int, eps: float = 1e-5):
+def encoder_forward(x32, layers, batch: int, seq: int, heads: int, eps: float = 1e-5, edges: str = "stored"):
     """Post-LayerNorm encoder stack.
 
     x32 [batch*seq, H] fp32 hidden states.  The residual stream is fp32; the
     GEMM inputs are split-bf16 pairs (hi + lo, ~16 significant bits); the packed
     qkv tensor that attention reads is plain bf16.  Returns fp64 [batch*seq, H].
+
+    ``edges="stored"`` rounds where the GPU graph stores a reduced-precision tensor;
+    ``edges="none"`` rounds nowhere: the chain's plain definition in fp64, used to
+    state how far the stored-edge graph (and the GPU) is from it.
     """
+    if edges not in ("stored", "none"):
+        raise ValueError("edges must be 'stored' or 'none'")
+    if edges == "none":
+        keep = lambda a: np.asarray(a, dtype=np.float64)
+        return _encoder(x32, layers, batch, seq, heads, eps, keep, keep)
+    return _encoder(x32, layers, batch, seq, heads, eps, ops.round_bf16x2, ops.round_bf16)
+
+
+def _encoder(x32, layers, batch, seq, heads, eps, pair, single):
+    """``pair`` is applied on the split-bf16 edges, ``single`` on the bf16 edge."""
     h = np.asarray(x32, dtype=np.float64)
     T, H = h.shape
     assert T == batch * seq and H % heads == 0
     d = H // heads
     for L in layers:
         f64 = lambda name: L[name].astype(np.float64)
-        hs = ops.round_bf16x2(h)                                         # split-bf16 edge
+        hs = pair(h)                                                     # split-bf16 edge
         qkv = ops.bias_act(ops.gemm(hs, L["w_qkv"]), f64("b_qkv"), gelu=False)
-        qkv = ops.round_bf16(qkv)                                        # bf16 edge
+        qkv = single(qkv)                                                # bf16 edge
         qkv4 = qkv.reshape(batch, seq, 3, heads, d)
         att = ops.attention(qkv4[:, :, 0], qkv4[:, :, 1], qkv4[:, :, 2], 1.0 / math.sqrt(d))
-        att_s = ops.round_bf16x2(att.reshape(T, H))                      # split-bf16 edge
+        att_s = pair(att.reshape(T, H))                                  # split-bf16 edge
         r1 = ops.bias_act(ops.gemm(att_s, L["w_o"]), f64("b_o"), gelu=False) + h
         h1 = ops.layernorm(r1, f64("ln1_g"), f64("ln1_b"), eps)          # fp32 edge
-        f = ops.bias_act(ops.gemm(ops.round_bf16x2(h1), L["w_1"]), f64("b_1"), gelu=True)
-        f_s = ops.round_bf16x2(f)                                        # split-bf16 edge
+        f = ops.bias_act(ops.gemm(pair(h1), L["w_1"]), f64("b_1"), gelu=True)
+        f_s = pair(f)                                                    # split-bf16 edge
         r2 = ops.bias_act(ops.gemm(f_s, L["w_2"]), f64("b_2"), gelu=False) + h1
         h = ops.layernorm(r2, f64("ln2_g"), f64("ln2_b"), eps)           # fp32 edge
     return h

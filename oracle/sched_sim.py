@@ -18,7 +18,9 @@ What is modelled, in the paper's order:
   idle (nothing queued, nothing in flight) and whose per-group timers have
   expired; once the owner submits, later atoms of the thief use only its own
   quota, atoms already in flight run to completion (Section 4.3 'TPC
-  Stealing', Section 4.4 second paragraph of 'Operation').
+  Stealing', Section 4.4 second paragraph of 'Operation').  Such an atom
+  boundary, where a kernel's next atom runs on fewer groups than its previous
+  one, is counted as a revocation.
 * prediction: per launch queue, keyed by the ordinal of the kernel since the
   last synchronisation and by the CU count; unseen CU counts scale the
   nearest known one linearly (Section 4.7).
@@ -113,6 +115,7 @@ class Tenant:
     next_ordinal: int = 0
     outstanding: int = 0
     last_end: float = 0.0                            # device-side stream order
+    cur_mask: Optional[FrozenSet[int]] = None        # CU groups of the current kernel's latest atom
     predictor: Predictor = None
 
     def idle(self) -> bool:
@@ -140,13 +143,15 @@ class Simulator:
         self.kernel_done: Dict[int, float] = {}
         self.kernel_submit: Dict[int, float] = {}
         self.kernel_blocks_seen: Dict[int, List[int]] = {}
-        self.stats = dict(atoms=0, steals=0, mispredicts=0, predictions=0)
+        self.stats = dict(atoms=0, steals=0, revocations=0, mispredicts=0, predictions=0)
+        self.per_tenant: List[Dict[str, int]] = []
 
     # ---- set-up ----------------------------------------------------------
     def add_tenant(self, quota, hp: bool) -> int:
         t = Tenant(tid=len(self.tenants), hp=hp, quota=frozenset(quota),
                    predictor=Predictor(self.cfg.ema_alpha))
         self.tenants.append(t)
+        self.per_tenant.append(dict(atoms=0, steals=0, revocations=0))
         return t.tid
 
     def submit_at(self, time: float, tid: int, kernel: Kernel) -> int:
@@ -209,6 +214,7 @@ class Simulator:
             t.cur.ordinal = t.next_ordinal
             t.next_ordinal += 1
             t.next_block = 0
+            t.cur_mask = None
         k = t.cur
         mask, stolen = self._choose_mask(t)
         cus = len(mask) * self.cfg.cus_per_group
@@ -234,8 +240,14 @@ class Simulator:
         for g in mask:
             self.group_free_at[g] = atom.t_end
         self.trace.append(atom)
-        self.stats["atoms"] += 1
-        self.stats["steals"] += int(stolen)
+        # revocation (Section 4.4 'Operation', second paragraph): the kernel's previous atom ran on
+        # groups that this one no longer gets - lent CUs went back at the atom boundary
+        revoked = t.cur_mask is not None and len(t.cur_mask - mask) > 0
+        t.cur_mask = mask
+        for book in (self.stats, self.per_tenant[t.tid]):
+            book["atoms"] += 1
+            book["steals"] += int(stolen)
+            book["revocations"] += int(revoked)
         self._push(atom.t_end, "complete", atom)
         return True
 

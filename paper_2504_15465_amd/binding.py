@@ -66,7 +66,7 @@ class RightsizeResult(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [("kernels", C.c_uint64), ("atoms", C.c_uint64), ("stolen_atoms", C.c_uint64),
-                ("predictions", C.c_uint64), ("mispredicts", C.c_uint64), ("abs_err_sum_us", C.c_double)]
+                ("revocations", C.c_uint64), ("predictions", C.c_uint64), ("mispredicts", C.c_uint64), ("abs_err_sum_us", C.c_double)]
 
 
 class CoreAtom(C.Structure):
@@ -82,7 +82,7 @@ EXPORTS = [
     "lithos_op_grid", "lithos_gemm_split_hint", "lithos_launch_atomized", "lithos_launch_atom", "lithos_partition_sync",
     "lithos_debug_block_counters", "lithos_rightsize", "lithos_time_launch",
     "lithos_tenant_create", "lithos_tenant_destroy", "lithos_submit", "lithos_sync_mark", "lithos_sync",
-    "lithos_poll", "lithos_tenant_stats",
+    "lithos_poll", "lithos_tenant_stats", "lithos_stats",
     "lithos_drive_open_loop", "lithos_drive_closed_loop_start", "lithos_drive_closed_loop_stop",
     "lithos_core_create", "lithos_core_destroy", "lithos_core_add_tenant", "lithos_core_submit",
     "lithos_core_sync_mark", "lithos_core_next_atom", "lithos_core_complete", "lithos_core_stats",
@@ -395,6 +395,12 @@ def lithos_poll(t, ticket) -> bool:
 def lithos_tenant_stats(t) -> Stats:
     s = Stats()
     _check(lib().lithos_tenant_stats(t, C.byref(s)))
+    return s
+
+
+def lithos_stats(ctx) -> Stats:
+    s = Stats()
+    _check(lib().lithos_stats(ctx, C.byref(s)))
     return s
 
 

@@ -466,30 +466,33 @@ int lithos_launch_atomized(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3
     int rc = op_plan(*op, &plan);
     if (rc != LITHOS_OK) return rc;
     if (grid.x || grid.y || grid.z) {
+        // Atoms are ranges of the linear index z*gy*gx + y*gx + x, which covers [0, total) in the
+        // same order for every factorisation: only the total has to agree.  The operator's own
+        // grid (tile geometry, K slices on z) is what the kernels un-flatten that index with.
         uint64_t t = (uint64_t)grid.x * grid.y * grid.z;
         if (t != plan.total) return fail(LITHOS_EINVAL, "lithos_launch_atomized: grid has %llu blocks, the operator has %u", (unsigned long long)t, plan.total);
-        plan.grid = grid;       // caller's factorisation of the same total
     }
     if ((rc = check_counters(ctx, plan)) != LITHOS_OK) return rc;
     hipStream_t s = part ? part->stream : ctx->plain;
     hipStream_t user = (hipStream_t)stream;
-    if (user && user != s) {
+    const bool hop = user && user != s;
+    std::lock_guard<std::mutex> lk(ctx->launch_mu);
+    if (hop) {
         LITHOS_HIP(hipEventRecord(ctx->ev_in, user));
         LITHOS_HIP(hipStreamWaitEvent(s, ctx->ev_in, 0));
     }
     const uint32_t total = plan.total;
     const uint32_t B = (atom_blocks == 0 || atom_blocks >= total) ? total : atom_blocks;
     const int dies = part ? part->n_dies : ctx->n_xcd;
-    for (uint32_t lo = 0; lo < total; lo += B) {
-        uint32_t hi = std::min(lo + B, total);
-        rc = op_launch(*op, plan, make_atom(ctx, plan, lo, hi, dies), s);
-        if (rc != LITHOS_OK) return rc;
+    for (uint32_t lo = 0; lo < total && rc == LITHOS_OK; lo += B)
+        rc = op_launch(*op, plan, make_atom(ctx, plan, lo, std::min(lo + B, total), dies), s);
+    if (hop) {
+        // also after a failed launch: the caller's stream must not overtake the atoms already queued
+        hipError_t e = hipEventRecord(ctx->ev_out, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(user, ctx->ev_out, 0);
+        if (e != hipSuccess && rc == LITHOS_OK) rc = fail(LITHOS_EHIP, "lithos_launch_atomized: %s", hipGetErrorString(e));
     }
-    if (user && user != s) {
-        LITHOS_HIP(hipEventRecord(ctx->ev_out, s));
-        LITHOS_HIP(hipStreamWaitEvent(user, ctx->ev_out, 0));
-    }
-    return LITHOS_OK;
+    return rc;
 }
 
 int lithos_partition_sync(lithos_ctx_t* ctx, const lithos_partition_t* part)

@@ -15,7 +15,9 @@ struct lithos_ctx {
     bool mask_interleaved = true;         // CU-mask bit i -> die i % n_xcd (else i / cu_per_xcd)
     int probe_d0 = 0, probe_other = 0;    // what the numbering probe saw
     hipStream_t plain = nullptr;          // unmasked queue for part == NULL
-    hipEvent_t ev_in = nullptr, ev_out = nullptr;
+    hipEvent_t ev_in = nullptr, ev_out = nullptr;   // ordering-stream hand-over of lithos_launch_atomized
+    std::mutex launch_mu;                 // serialises lithos_launch_atomized (one event pair per context)
+    std::atomic<uint64_t> pt_kernels{0};  // kernels of pass-through tenants (launched whole at submission)
     uint32_t* counters = nullptr;         // exactly-once instrumentation (device)
     uint32_t n_counters = 0;
     std::atomic<int> live_tenants{0};

@@ -428,6 +428,7 @@ int lithos_submit(lithos_tenant_t* t, const lithos_op_t* op, uint64_t* ticket_ou
         if (e != hipSuccess) return fail(LITHOS_EHIP, "pass-through completion event: %s", hipGetErrorString(e));
         t->fly.push_back(f);
         t->submitted.fetch_add(1);
+        t->ctx->pt_kernels.fetch_add(1);
         t->pt_stats.kernels++;
         t->pt_stats.atoms++;
         if (ticket_out) *ticket_out = f.kernel_done;
@@ -498,6 +499,20 @@ int lithos_tenant_stats(lithos_tenant_t* t, lithos_stats_t* out)
     Scheduler* s = t->ctx->sched;
     std::lock_guard<std::mutex> lk(s->mu);
     *out = s->core.stats(t->core_idx);
+    return LITHOS_OK;
+}
+
+int lithos_stats(lithos_ctx_t* ctx, lithos_stats_t* out)
+{
+    if (!ctx || !out) return fail(LITHOS_EINVAL, "lithos_stats: null argument");
+    memset(out, 0, sizeof *out);
+    if (Scheduler* s = ctx->sched) {
+        std::lock_guard<std::mutex> lk(s->mu);
+        *out = s->core.totals();
+    }
+    const uint64_t pt = ctx->pt_kernels.load();     // pass-through kernels: one whole launch each
+    out->kernels += pt;
+    out->atoms += pt;
     return LITHOS_OK;
 }
 

@@ -135,6 +135,7 @@ bool Core::next_atom(int ti, double now_us, lithos_core_atom_t* out)
         t.cur.ordinal = t.next_ordinal++;
         t.next_block = 0;
         t.has_cur = true;
+        t.prev_mask = 0;
         t.stats.kernels++;
     }
     const CoreKernel& k = t.cur;
@@ -179,6 +180,9 @@ bool Core::next_atom(int ti, double now_us, lithos_core_atom_t* out)
     t.outstanding++;
     t.stats.atoms++;
     if (stolen) t.stats.stolen_atoms++;
+    // an atom boundary at which borrowed groups went back (Section 4.4 'Operation')
+    if (t.prev_mask & ~mask) t.stats.revocations++;
+    t.prev_mask = mask;
     // per-group timers from the prediction (unknown: one atom_duration)
     const double hold = has_pred ? pred : cfg_.atom_duration_us;
     for (size_t g = 0; g < group_cus_.size(); ++g)
@@ -187,6 +191,21 @@ bool Core::next_atom(int ti, double now_us, lithos_core_atom_t* out)
             busy_by_[g] = ti;
         }
     return true;
+}
+
+lithos_stats_t Core::totals() const
+{
+    lithos_stats_t s{};
+    for (const CoreTenant& t : tenants_) {
+        s.kernels += t.stats.kernels;
+        s.atoms += t.stats.atoms;
+        s.stolen_atoms += t.stats.stolen_atoms;
+        s.revocations += t.stats.revocations;
+        s.predictions += t.stats.predictions;
+        s.mispredicts += t.stats.mispredicts;
+        s.abs_err_sum_us += t.stats.abs_err_sum_us;
+    }
+    return s;
 }
 
 bool Core::complete(uint64_t atom_id, double now_us, double measured_us, uint64_t* kernel_done)

@@ -47,6 +47,7 @@ struct CoreTenant {
     int next_ordinal = 0;
     int outstanding = 0;
     int queued_kernels = 0;             // kernels (not sync marks) in `queue`
+    uint32_t prev_mask = 0;             // groups of the current kernel's previous atom (0: none launched yet)
     Predictor predictor;
     lithos_stats_t stats{};
     explicit CoreTenant(double alpha) : predictor(alpha) {}
@@ -77,6 +78,7 @@ public:
     // this atom finished, or 0
     bool complete(uint64_t atom_id, double now_us, double measured_us, uint64_t* kernel_done);
     const lithos_stats_t& stats(int tenant) const { return tenants_[tenant].stats; }
+    lithos_stats_t totals() const;
     int n_tenants() const { return (int)tenants_.size(); }
     int n_groups() const { return (int)group_cus_.size(); }
     int cus_of(uint32_t group_mask) const;

@@ -49,7 +49,7 @@ def test_binding_struct_sizes_match_the_header_layout():
     assert C.sizeof(B.Dim3) == 12
     assert C.sizeof(B.Config) == 40
     assert C.sizeof(B.CoreAtom) == 56
-    assert C.sizeof(B.Stats) == 48
+    assert C.sizeof(B.Stats) == 56
 
 
 def test_core_rejects_bad_arguments():
@@ -203,6 +203,15 @@ def test_policy_core_matches_oracle_model_step_by_step(atomize, steal, atom_us, 
     s_hp, s_be = B.lithos_core_stats(h.c, h.hp), B.lithos_core_stats(h.c, h.be)
     assert s_hp.atoms + s_be.atoms == sim.stats["atoms"]
     assert s_hp.stolen_atoms + s_be.stolen_atoms == sim.stats["steals"]
+    assert (s_hp.revocations, s_be.revocations) == (sim.per_tenant[hp]["revocations"], sim.per_tenant[be]["revocations"])
+    assert (s_hp.stolen_atoms, s_be.stolen_atoms) == (sim.per_tenant[hp]["steals"], sim.per_tenant[be]["steals"])
+    if atomize and steal and atom_us <= 100.0:
+        assert s_be.revocations > 0          # the scenario does hand CUs back at atom boundaries
+    elif atomize and steal:
+        pass                                 # 400 us atoms: these kernels are predicted shorter and stay whole
+    else:
+        assert s_be.revocations == 0         # whole kernels have no inner boundary; no lending, nothing to revoke
+    assert s_hp.revocations == 0             # the best-effort tenant never idles, so nothing is lent to the other
     assert s_hp.mispredicts + s_be.mispredicts == sim.stats["mispredicts"]
     assert s_hp.predictions + s_be.predictions == sim.stats["predictions"]
     B.lithos_core_destroy(h.c)
@@ -259,6 +268,10 @@ def test_policy_core_matches_oracle_model_with_three_tenants(atomize, steal):
         assert st == (m != own)
         if not steal:
             assert m == own
+    for who in range(3):
+        st = B.lithos_core_stats(h.c, h.ids[who])
+        book = sim.per_tenant[sim_ids[who]]
+        assert (st.atoms, st.stolen_atoms, st.revocations) == (book["atoms"], book["steals"], book["revocations"])
     if steal:
         stolen_by = {t for t, *_rest in [(g[0], g[5]) for g in got if g[5]]}
         assert sim_ids[2] in stolen_by                      # best effort lives on lent CUs

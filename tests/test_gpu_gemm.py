@@ -418,3 +418,47 @@ def test_split_bf16_output_of_plain_bf16_gemm(tile, k):
     assert bits_equal(pair[0], single)
     got = pair[0].cpu().to(torch.float64).numpy() + pair[1].cpu().to(torch.float64).numpy()
     assert np.abs(got - ref).max() <= 2.0 ** -15 * np.abs(ref).max() + 2.0 ** -22 * k
+
+
+@pytest.mark.parametrize("grid", [(64, 1, 1), (4, 16, 1), (1, 8, 8), (2, 2, 16)])
+def test_callers_grid_of_the_same_total_changes_nothing(grid):
+    """Atoms are ranges of the linear block index; another factorisation of the same total numbers
+    the blocks alike, so the result equals the default launch and every block runs once."""
+    m = n = k = 512
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=0)
+    a, b = dev_bits(a_bits), dev_bits(b_bits)
+    c0, c1 = nan_like((m, n), torch.float32), nan_like((m, n), torch.float32)
+    torch.cuda.synchronize()
+    B.lithos_launch_atomized(ctx(), B.gemm_op(a, b, c0, m, n, k, tile=64), (0, 0, 0), 0, None, None)
+    cnt = counters(64)
+    B.lithos_debug_block_counters(ctx(), cnt)
+    try:
+        B.lithos_launch_atomized(ctx(), B.gemm_op(a, b, c1, m, n, k, tile=64), grid, 8, None, None)
+        B.lithos_partition_sync(ctx(), None)
+    finally:
+        B.lithos_debug_block_counters(ctx(), None)
+    assert cnt.cpu().tolist() == [1] * 64
+    assert not torch.isnan(c1).any()
+    assert bits_equal(c0, c1)
+    assert rel_fro(c1, O.gemm(a_bits, b_bits)) <= 1e-4
+    with pytest.raises(B.LithosError) as e:
+        B.lithos_launch_atomized(ctx(), B.gemm_op(a, b, c1, m, n, k, tile=64), (8, 7, 1), 8, None, None)
+    assert e.value.code == B.EINVAL
+
+
+def test_k_sliced_gemm_keeps_its_slices_under_a_callers_grid():
+    """The K slices live on the operator's z axis; a caller's flat grid of the same total must not lose them."""
+    m, n, k, S = 256, 256, 1024, 2
+    a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=5)
+    a, b = dev_bits(a_bits), dev_bits(b_bits)
+    p0, p1 = nan_like((S, m, n), torch.float32), nan_like((S, m, n), torch.float32)
+    op0 = B.gemm_op(a, b, p0, m, n, k, tile=128, k_slices=S)
+    grid, _ = B.lithos_op_grid(ctx(), op0)
+    total = grid[0] * grid[1] * grid[2]
+    assert grid[2] == S
+    torch.cuda.synchronize()
+    B.lithos_launch_atomized(ctx(), op0, (0, 0, 0), 0, None, None)
+    B.lithos_launch_atomized(ctx(), B.gemm_op(a, b, p1, m, n, k, tile=128, k_slices=S), (total, 1, 1), 3, None, None)
+    B.lithos_partition_sync(ctx(), None)
+    assert not torch.isnan(p1).any()
+    assert bits_equal(p0, p1)

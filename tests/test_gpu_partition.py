@@ -148,3 +148,41 @@ def test_ordering_stream_chains_launches_on_different_partitions():
     finally:
         for p in parts:
             B.lithos_destroy_partition(p)
+
+
+def test_two_threads_launch_on_one_context_with_their_own_ordering_streams():
+    """lithos_launch_atomized is serialised inside the library: two host threads, each chaining its
+    kernels over two partitions through its own stream, get the bits of the single-queue runs."""
+    import threading
+    from paper_2504_15465_amd.models import MlpChain, run_ops
+    c = ctx()
+    parts = [B.lithos_create_partition(c, B.lithos_make_mask(c, 64, B.MASK_STRIPED, first)) for first in (0, 64, 128, 192)]
+    try:
+        chains, refs = [], []
+        for i in range(2):
+            ch = MlpChain(inputs.mlp_params(3, 1024, seed=1 + i), 8)
+            ch.set_input(inputs.mlp_requests(pool=1, batch=8, hidden=1024, seed=2 + i)[0])
+            run_ops(c, ch.ops(), parts[0])
+            chains.append(ch)
+            refs.append(ch.out.clone())
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        torch.cuda.synchronize()
+        bad = []
+
+        def work(i):
+            ops = chains[i].ops()
+            for rep in range(40):
+                for j, op in enumerate(ops):
+                    B.lithos_launch_atomized(c, op, (0, 0, 0), 3 if j % 2 else 0, parts[2 * i + j % 2], streams[i].cuda_stream)
+                with torch.cuda.stream(streams[i]):
+                    snap = chains[i].out.clone()
+                streams[i].synchronize()
+                if not bits_equal(snap, refs[i]):
+                    bad.append((i, rep))
+        th = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+        [t.start() for t in th]
+        [t.join() for t in th]
+        assert not bad, bad[:5]
+    finally:
+        for p in parts:
+            B.lithos_destroy_partition(p)

@@ -87,6 +87,48 @@ def test_stacked_tenants_bit_exact_and_stats(steal, atomize):
             assert s_be.stolen_atoms > 0              # idle high-priority CUs were lent
         else:
             assert s_be.stolen_atoms == 0 and s_hp.stolen_atoms == 0
+        # a revocation is an inner atom boundary of a kernel: none without atoms or without lending
+        assert s_be.revocations <= s_be.atoms - s_be.kernels
+        if not (steal and atomize):
+            assert s_be.revocations == 0 and s_hp.revocations == 0
+        tot = B.lithos_stats(c)
+        for f in ("kernels", "atoms", "stolen_atoms", "revocations", "predictions", "mispredicts"):
+            assert getattr(tot, f) == getattr(s_be, f) + getattr(s_hp, f), f
+    finally:
+        drop_world(c, [p_hp, p_be], [t_hp, t_be])
+
+
+def test_lent_cus_go_back_at_the_next_atom_boundary():
+    """A long best-effort kernel runs on its quota plus the idle high-priority CUs; a high-priority kernel
+    submitted in the middle of it gets them back at the next atom boundary, which the context counts as a
+    revocation (Section 4.4 'Operation'); once the high-priority tenant is idle again they are lent again."""
+    cfg = B.Config.default(atom_duration_us=100.0, max_outstanding=1, max_outstanding_hp=16, steal=1, atomize=1)
+    c, p_hp, p_be = make_world(cfg)
+    t_hp = B.lithos_tenant_create(c, B.CLASS_HP, p_hp)
+    t_be = B.lithos_tenant_create(c, B.CLASS_BE, p_be)
+    try:
+        long_op = B.spin_op(16384, 5000)              # 50 us per block, 2 per CU: 32 waves on 256 CUs, > 1.6 ms
+        tiny = B.spin_op(8, 100)
+        for _ in range(3):                            # the predictor learns the kernel on the wide mask
+            B.lithos_submit(t_be, long_op)
+            B.lithos_sync(t_be)
+        assert B.lithos_tenant_stats(t_be).revocations == 0
+        seen = 0
+        for attempt in range(5):
+            before = B.lithos_tenant_stats(t_be)
+            B.lithos_submit(t_be, long_op)
+            time.sleep(0.0005)
+            B.lithos_submit(t_hp, tiny)
+            B.lithos_sync(t_hp)
+            B.lithos_sync(t_be)
+            after = B.lithos_tenant_stats(t_be)
+            assert after.atoms - before.atoms >= 4    # the kernel was cut
+            seen += after.revocations - before.revocations
+            if seen:
+                break
+        assert 1 <= seen <= 2
+        assert B.lithos_tenant_stats(t_hp).revocations == 0
+        assert B.lithos_stats(c).revocations == seen
     finally:
         drop_world(c, [p_hp, p_be], [t_hp, t_be])
 
@@ -101,6 +143,8 @@ def test_open_loop_driver_and_passthrough_tenants():
         assert lat.shape == (200,) and np.all(lat > 5.0) and np.median(lat) < 500.0
         s = B.lithos_tenant_stats(t_hp)
         assert s.kernels == 200 and s.atoms == 200
+        tot = B.lithos_stats(c)                                # pass-through kernels count in the context totals
+        assert tot.kernels == 200 and tot.atoms == 200 and tot.stolen_atoms == 0 and tot.revocations == 0
     finally:
         B.lithos_tenant_destroy(t_hp)
         B.lithos_shutdown(c)

@@ -155,3 +155,41 @@ def test_unseen_cu_count_scales_linearly():
     assert p.us_per_block(0, 128) == 1.0        # half the CUs: twice as long
     p.update(0, 256, 100, 90.0)                 # EMA: 0.75*0.5 + 0.25*0.9
     assert abs(p.us_per_block(0, 256) - 0.6) < 1e-12
+
+
+def _revocations_from_trace(sim, tenant):
+    """Recount from the atom trace: boundaries inside one kernel where the mask lost groups."""
+    by_kernel = {}
+    for a in sim.trace:
+        if a.tenant == tenant:
+            by_kernel.setdefault(a.kid, []).append(a.mask)
+    return sum(1 for masks in by_kernel.values() for m0, m1 in zip(masks, masks[1:]) if m0 - m1)
+
+
+def test_revocations_count_atom_boundaries_where_lent_groups_go_back():
+    """One long best-effort kernel per batch, cut in atoms; a high-priority request that arrives in the
+    middle of a kernel takes its groups back at the next atom boundary: exactly one revocation per such
+    arrival, none without arrivals, none when kernels stay whole or nothing is lent."""
+    cfg = SimConfig(atom_duration_us=50.0, max_outstanding=1)
+    # warm the predictor with two kernels, then one arrival inside the fourth kernel
+    sim, hp, be, _ = build(cfg, be_kernels=6, hp_times=[])
+    sim.run()
+    assert sim.stats["revocations"] == 0 and sim.stats["steals"] > 0
+    sim, hp, be, _ = build(cfg, be_kernels=6, hp_times=[700.0])
+    sim.run()
+    cut = [a for a in sim.trace if a.tenant == be and a.t_launch <= 700.0 < a.t_end]
+    assert cut and cut[0].stolen and cut[0].hi < 1024         # the arrival falls inside a stolen, inner atom
+    assert sim.per_tenant[be]["revocations"] == 1
+    assert sim.per_tenant[hp]["revocations"] == 0
+    assert sim.stats["revocations"] == _revocations_from_trace(sim, be) == 1
+    # many arrivals: the count equals the recount from the trace
+    rnd = random.Random(5)
+    times = sorted(rnd.uniform(300.0, 6000.0) for _ in range(12))
+    sim, hp, be, _ = build(cfg, be_kernels=30, hp_times=times)
+    sim.run()
+    assert sim.per_tenant[be]["revocations"] == _revocations_from_trace(sim, be) > 0
+    assert sim.per_tenant[be]["revocations"] <= len(times)
+    for off in (dict(atomize=False), dict(steal=False)):
+        sim, hp, be, _ = build(SimConfig(atom_duration_us=50.0, max_outstanding=1, **off), be_kernels=30, hp_times=times)
+        sim.run()
+        assert sim.stats["revocations"] == 0
