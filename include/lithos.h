@@ -235,6 +235,24 @@ int lithos_gemm_split_hint(const lithos_op_t* op, int32_t n_cus, int32_t* tile_o
 int lithos_launch_atomized(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3 grid,
                            uint32_t atom_blocks, const lithos_partition_t* part, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): split decode attention with the library's own workspace.
+ * `op` is an ATTN_DEC descriptor with splits >= 2 and in[3] == NULL.  The key ranges' partial
+ * softmaxes go to a fixed device array inside the library instead of a caller's workspace, and the
+ * merge step follows on the same queue: the call does what lithos_launch_atomized(ATTN_DEC with a
+ * workspace) followed by lithos_launch_atomized(ATTN_MERGE) does, with the same kernels and bit for
+ * bit the same out[0].  atom_blocks cuts the ATTN_DEC launch as in lithos_launch_atomized (the
+ * merge runs whole); part and stream have the same meaning as there.
+ * Limit: batch * n_q * splits * (d + 2) <= LITHOS_STATIC_SCRATCH_FLOATS, else LITHOS_ELIMIT and
+ * nothing is launched.  The array (8 MiB per GPU the library was initialised on, held until the
+ * process ends) is shared by every call on that GPU and keeps the last call's contents; nothing in
+ * it has to start at zero, since every slot that the merge reads is written first.  Calls that
+ * overlap on one GPU (from two threads, or on two partitions without a common ordering stream)
+ * race on it: the caller serialises them.  The call itself allocates and frees nothing. */
+#define LITHOS_STATIC_SCRATCH_FLOATS (2u << 20)
+int lithos_launch_attn_dec_static(lithos_ctx_t* ctx, const lithos_op_t* op, uint32_t atom_blocks,
+                                  const lithos_partition_t* part, void* stream);
+
 /* Same, for an explicit block range [lo,hi) only (one atom). */
 int lithos_launch_atom(lithos_ctx_t* ctx, const lithos_op_t* op, uint32_t lo, uint32_t hi,
                        const lithos_partition_t* part);

@@ -79,7 +79,8 @@ EXPORTS = [
     "lithos_init", "lithos_shutdown", "lithos_device_info", "lithos_last_error",
     "lithos_make_mask", "lithos_create_partition", "lithos_destroy_partition", "lithos_partition_cus",
     "lithos_partition_stream", "lithos_probe_partition", "lithos_partitions_coupled",
-    "lithos_op_grid", "lithos_gemm_split_hint", "lithos_launch_atomized", "lithos_launch_atom", "lithos_partition_sync",
+    "lithos_op_grid", "lithos_gemm_split_hint", "lithos_launch_atomized", "lithos_launch_attn_dec_static",
+    "lithos_launch_atom", "lithos_partition_sync",
     "lithos_debug_block_counters", "lithos_rightsize", "lithos_time_launch",
     "lithos_tenant_create", "lithos_tenant_destroy", "lithos_submit", "lithos_sync_mark", "lithos_sync",
     "lithos_poll", "lithos_tenant_stats", "lithos_stats",
@@ -328,6 +329,14 @@ def lithos_launch_atomized(ctx, op: Op, grid=(0, 0, 0), atom_blocks=0, part=None
     g = Dim3(*grid)
     _check(lib().lithos_launch_atomized(ctx, C.byref(op), g, C.c_uint32(atom_blocks), part,
                                         C.c_void_p(stream) if stream else None))
+
+
+STATIC_SCRATCH_FLOATS = 2 << 20
+
+
+def lithos_launch_attn_dec_static(ctx, op: Op, atom_blocks=0, part=None, stream=None):
+    _check(lib().lithos_launch_attn_dec_static(ctx, C.byref(op), C.c_uint32(atom_blocks), part,
+                                               C.c_void_p(stream) if stream else None))
 
 
 def lithos_launch_atom(ctx, op: Op, lo, hi, part=None):

@@ -31,6 +31,28 @@ int fail(int code, const char* fmt, ...)
     return code;
 }
 
+// ---- workspace for the entry point that allocates nothing ---------------------
+// File-scope device array; each GPU holds its own copy at its own address.  In host code the
+// array's name is only a stand-in for the symbol: its device address is asked for once per
+// device (static_scratch_setup, called by lithos_init with that device current) and only that
+// address is ever handed to kernels.
+static __device__ __align__(256) __attribute__((used)) float scratch[LITHOS_STATIC_SCRATCH_FLOATS];
+static const int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices] = {nullptr};
+static std::mutex g_scratch_mu;
+
+static int static_scratch_setup(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(LITHOS_ELIMIT, "device ordinal %d beyond %d", device, kMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (g_scratch_ptr[device]) return LITHOS_OK;
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(LITHOS_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", device, hipGetErrorString(e));
+    g_scratch_ptr[device] = static_cast<float*>(p);
+    return LITHOS_OK;
+}
+
 // ---- probe kernel: which die / CU does each workgroup run on ---------------
 __global__ __launch_bounds__(64) void probe_kernel(uint32_t* xcd, uint32_t* hwid, uint64_t ticks)
 {
@@ -223,7 +245,8 @@ int lithos_init(int device, const lithos_config_t* cfg, lithos_ctx_t** out)
     e = hipEventCreateWithFlags(&ctx->ev_in, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_out, hipEventDisableTiming);
     if (e != hipSuccess) { delete ctx; return fail(LITHOS_EHIP, "hipEventCreateWithFlags: %s", hipGetErrorString(e)); }
-    int rc = detect_mask_layout(ctx);
+    int rc = static_scratch_setup(device);
+    if (rc == LITHOS_OK) rc = detect_mask_layout(ctx);
     if (rc != LITHOS_OK) {
         (void)hipStreamDestroy(ctx->plain);
         (void)hipEventDestroy(ctx->ev_in);
@@ -491,6 +514,59 @@ int lithos_launch_atomized(lithos_ctx_t* ctx, const lithos_op_t* op, lithos_dim3
         hipError_t e = hipEventRecord(ctx->ev_out, s);
         if (e == hipSuccess) e = hipStreamWaitEvent(user, ctx->ev_out, 0);
         if (e != hipSuccess && rc == LITHOS_OK) rc = fail(LITHOS_EHIP, "lithos_launch_atomized: %s", hipGetErrorString(e));
+    }
+    return rc;
+}
+
+int lithos_launch_attn_dec_static(lithos_ctx_t* ctx, const lithos_op_t* op, uint32_t atom_blocks,
+                                  const lithos_partition_t* part, void* stream)
+{
+    if (!ctx || !op) return fail(LITHOS_EINVAL, "lithos_launch_attn_dec_static: null argument");
+    if (op->kind != LITHOS_OP_ATTN_DEC) return fail(LITHOS_EINVAL, "lithos_launch_attn_dec_static: operator kind %d is not ATTN_DEC", op->kind);
+    if (op->dim[6] < 2) return fail(LITHOS_EINVAL, "lithos_launch_attn_dec_static: needs splits >= 2 (an unsplit launch uses no workspace)");
+    if (op->in[3]) return fail(LITHOS_EINVAL, "lithos_launch_attn_dec_static: in[3] must be NULL, the workspace is the library's");
+    float* ws = g_scratch_ptr[ctx->device];
+    if (!ws) return fail(LITHOS_ESTATE, "lithos_launch_attn_dec_static: no workspace address for device %d", ctx->device);
+    (void)hipSetDevice(ctx->device);
+    lithos_op_t dec = *op, merge{};
+    dec.in[3] = ws;
+    OpPlan pd, pm;
+    int rc = op_plan(dec, &pd);             // validates shapes before the size is computed from them
+    if (rc != LITHOS_OK) return rc;
+    const uint64_t need = (uint64_t)dec.dim[0] * (uint64_t)dec.dim[1] * (uint64_t)dec.dim[6] * (uint64_t)(dec.dim[3] + 2);
+    if (need > LITHOS_STATIC_SCRATCH_FLOATS)
+        return fail(LITHOS_ELIMIT, "lithos_launch_attn_dec_static: batch*n_q*splits*(d+2) = %llu floats, the fixed workspace holds %u",
+                    (unsigned long long)need, (unsigned)LITHOS_STATIC_SCRATCH_FLOATS);
+    merge.kind = LITHOS_OP_ATTN_MERGE;
+    merge.flags = dec.flags & LITHOS_F_OUT_F32;
+    merge.op_id = dec.op_id;
+    merge.dim[0] = dec.dim[0]; merge.dim[1] = dec.dim[1]; merge.dim[2] = dec.dim[2]; merge.dim[3] = dec.dim[3]; merge.dim[4] = dec.dim[6];
+    merge.in[0] = ws;
+    merge.out[0] = dec.out[0];
+    if ((rc = op_plan(merge, &pm)) != LITHOS_OK) return rc;
+    if ((rc = check_counters(ctx, pd)) != LITHOS_OK) return rc;
+    hipStream_t s = part ? part->stream : ctx->plain;
+    hipStream_t user = (hipStream_t)stream;
+    const bool hop = user && user != s;
+    const int dies = part ? part->n_dies : ctx->n_xcd;
+    std::lock_guard<std::mutex> lk(ctx->launch_mu);
+    if (hop) {
+        LITHOS_HIP(hipEventRecord(ctx->ev_in, user));
+        LITHOS_HIP(hipStreamWaitEvent(s, ctx->ev_in, 0));
+    }
+    const uint32_t total = pd.total;
+    const uint32_t B = (atom_blocks == 0 || atom_blocks >= total) ? total : atom_blocks;
+    for (uint32_t lo = 0; lo < total && rc == LITHOS_OK; lo += B)
+        rc = op_launch(dec, pd, make_atom(ctx, pd, lo, std::min(lo + B, total), dies), s);
+    if (rc == LITHOS_OK) {
+        AtomArgs whole = make_atom(ctx, pm, 0, pm.total, dies);
+        whole.counters = nullptr;           // the exactly-once counters, if set, describe the ATTN_DEC grid
+        rc = op_launch(merge, pm, whole, s);
+    }
+    if (hop) {
+        hipError_t e = hipEventRecord(ctx->ev_out, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(user, ctx->ev_out, 0);
+        if (e != hipSuccess && rc == LITHOS_OK) rc = fail(LITHOS_EHIP, "lithos_launch_attn_dec_static: %s", hipGetErrorString(e));
     }
     return rc;
 }
