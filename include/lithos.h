@@ -144,6 +144,16 @@ typedef struct lithos_config {
                                     remap themselves.  Same results bit for bit; kept to measure the
                                     early-exit traffic of Section 4.4 'Performance Optimizations' */
     double   ema_alpha;          /* Section 4.7 predictor smoothing; default 0.25 */
+    double   rightsize_slip;     /* Section 4.5 'Operation' in the dispatcher: latency slip k >= 1 (the paper
+                                    evaluates 1.1); 0 = off (default).  When a kernel could run on its quota
+                                    plus borrowed CUs, the occupancy filter (blocks / resident blocks per CU)
+                                    and the model l = m/t + b, fitted to the predictor's latencies of that
+                                    kernel on the two CU sets, decide whether the wider set is taken: it is
+                                    not if the kernel cannot fill more than the quota, or if the model puts
+                                    the quota within k of the wider set's latency.  Decided once per kernel;
+                                    its atoms inherit the choice.  The model needs the kernel's latency on
+                                    both sets: it borrows until the wider set has been measured, then runs
+                                    on the quota once. */
 } lithos_config_t;
 
 typedef struct lithos_devinfo {
@@ -276,6 +286,8 @@ typedef struct lithos_rightsize_result {
     int32_t occupancy_bound_cus; /* ceil(total blocks / resident blocks per CU), Section 4.5 'Filtering Outliers' */
     double  model_m, model_b;    /* l = m/t + b through the smallest and largest sweep points */
     int32_t model_cus;           /* smallest t with l(t) <= (1+slowdown) l(T) under that model */
+    int32_t online_cus;          /* Section 4.5 'Operation' with k = 1+slowdown: the occupancy bound if it is below
+                                    the largest count, else model_cus */
 } lithos_rightsize_result_t;
 
 /* Time `op` (unatomized) on striped masks of cu_lo, cu_lo+cu_step, ... cu_hi
@@ -306,6 +318,7 @@ typedef struct lithos_stats {
                                 had borrowed, because their owner has work again or their timers are not free
                                 (Section 4.4 'Operation', second paragraph: stealing stops for the thief's
                                 later atoms; atoms in flight run to completion) */
+    uint64_t rightsized_kernels; /* kernels that Section 4.5's rule kept on their quota although CUs could be borrowed */
     uint64_t predictions;    /* atoms launched with a prediction */
     uint64_t mispredicts;    /* |predicted - measured| > 50 us (Section 7.4) */
     double   abs_err_sum_us;

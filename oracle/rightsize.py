@@ -84,3 +84,52 @@ def r_squared(y: Sequence[float], yhat: Sequence[float]) -> float:
     ss_tot = sum((v - mean) ** 2 for v in y)
     ss_res = sum((v - w) ** 2 for v, w in zip(y, yhat))
     return 1.0 - ss_res / ss_tot if ss_tot > 0 else 1.0
+
+
+def fit_through(t1: float, l1: float, t2: float, l2: float) -> Tuple[float, float]:
+    """(m, b) of l = m/t + b passing through (t1, l1) and (t2, l2), t1 != t2.
+
+    Section 4.5 'Modeling Kernel Scaling' takes one unit and all units as the two points; on a
+    device where the smallest maskable set has more than one unit, the two points are whatever
+    two allocations have been measured."""
+    if t1 <= 0 or t2 <= 0 or t1 == t2:
+        raise ValueError("need two distinct positive unit counts")
+    m = (l1 - l2) / (1.0 / t1 - 1.0 / t2)
+    b = l2 - m / t2
+    return m, b
+
+
+def online_choice(total_blocks: int, blocks_per_unit: int, allocated: int, candidates: Sequence[int],
+                  measured: Dict[int, float], k: float) -> int:
+    """Section 4.5 'Operation' for one kernel, on a device that offers only the unit counts in
+    ``candidates`` (the CU sets a tenant has queues for), the largest being what the job holds.
+
+    1. Occupancy filter: if the kernel cannot fill the allocation (bound < allocated), it is
+       launched on the smallest candidate that still holds the bound (the largest candidate if
+       none does).
+    2. Otherwise the scaling model: with latencies measured at two of the candidates (``measured``
+       maps unit count -> latency of the whole kernel), fit l = m/t + b through the smallest and
+       the largest measured count, take the minimum t with l(t) <= k * l(allocated), and launch
+       on the smallest candidate >= that t.  The model needs the kernel's latency on two
+       allocations, which only running it there can give: while the allocation itself has not
+       been measured the kernel keeps it; once it has, and the smallest candidate has not, the
+       kernel runs there once.
+    """
+    cands = sorted(set(candidates))
+    if not cands or allocated != cands[-1]:
+        raise ValueError("the allocation must be the largest candidate")
+    if k < 1.0:
+        raise ValueError("latency slip k must be >= 1")
+    bound = occupancy_bound(total_blocks, blocks_per_unit)
+    if bound < allocated:
+        fits = [c for c in cands if c >= bound]
+        return fits[0] if fits else cands[-1]
+    known = sorted(c for c in measured if c in cands)
+    if allocated not in known:
+        return allocated
+    if len(known) < 2:
+        return cands[0] if len(cands) > 1 else allocated
+    t1, t2 = known[0], known[-1]
+    m, b = fit_through(t1, measured[t1], t2, measured[t2])
+    need = min_units_for_slip(m, b, allocated, k)
+    return min(c for c in cands if c >= need)

@@ -21,6 +21,10 @@ What is modelled, in the paper's order:
   Stealing', Section 4.4 second paragraph of 'Operation').  Such an atom
   boundary, where a kernel's next atom runs on fewer groups than its previous
   one, is counted as a revocation.
+* right-sizing (optional): when a kernel could borrow CUs, the occupancy
+  filter and the two-point scaling model decide whether the wider set is
+  worth taking; if not, the kernel and all its atoms stay on the quota
+  (Section 4.5 'Operation').
 * prediction: per launch queue, keyed by the ordinal of the kernel since the
   last synchronisation and by the CU count; unseen CU counts scale the
   nearest known one linearly (Section 4.7).
@@ -40,6 +44,7 @@ from dataclasses import dataclass, field
 from typing import Callable, Dict, FrozenSet, List, Optional, Tuple
 
 from . import atoms as atom_model
+from . import rightsize as rightsize_model
 
 MISPREDICT_US = 50.0   # Section 7.4: absolute error above 50 us is a misprediction
 
@@ -54,6 +59,7 @@ class SimConfig:
     steal: bool = True
     atomize: bool = True
     ema_alpha: float = 0.25
+    rightsize_slip: float = 0.0      # Section 4.5 latency slip k (>= 1); 0: no online right-sizing
 
 
 @dataclass
@@ -116,6 +122,7 @@ class Tenant:
     outstanding: int = 0
     last_end: float = 0.0                            # device-side stream order
     cur_mask: Optional[FrozenSet[int]] = None        # CU groups of the current kernel's latest atom
+    cur_narrow: bool = False                         # right-sizing keeps the current kernel on the quota
     predictor: Predictor = None
 
     def idle(self) -> bool:
@@ -151,7 +158,7 @@ class Simulator:
         t = Tenant(tid=len(self.tenants), hp=hp, quota=frozenset(quota),
                    predictor=Predictor(self.cfg.ema_alpha))
         self.tenants.append(t)
-        self.per_tenant.append(dict(atoms=0, steals=0, revocations=0))
+        self.per_tenant.append(dict(atoms=0, steals=0, revocations=0, rightsized=0))
         return t.tid
 
     def submit_at(self, time: float, tid: int, kernel: Kernel) -> int:
@@ -217,6 +224,21 @@ class Simulator:
             t.cur_mask = None
         k = t.cur
         mask, stolen = self._choose_mask(t)
+        if t.next_block == 0:
+            # Section 4.5 'Operation', once per kernel (its atoms inherit the allocation): the CU
+            # sets on offer are the quota and the quota plus what can be borrowed right now
+            t.cur_narrow = False
+            if stolen and self.cfg.rightsize_slip >= 1.0:
+                own = len(t.quota) * self.cfg.cus_per_group
+                wide = len(mask) * self.cfg.cus_per_group
+                row = t.predictor.table.get(k.ordinal, {})
+                measured = {c: row[c] * k.total_blocks for c in (own, wide) if c in row}
+                pick = rightsize_model.online_choice(k.total_blocks, k.wg_per_cu, wide, [own, wide],
+                                                     measured, self.cfg.rightsize_slip)
+                t.cur_narrow = pick == own
+                self.per_tenant[t.tid]["rightsized"] += int(t.cur_narrow)
+        if t.cur_narrow:
+            mask, stolen = frozenset(t.quota), False
         cus = len(mask) * self.cfg.cus_per_group
         blocks, pred = self._choose_blocks(t, k, cus)
         atom = Atom(aid=self._aid, tenant=t.tid, kid=k.kid, op=k.op, ordinal=k.ordinal,

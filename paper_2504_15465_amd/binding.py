@@ -41,11 +41,12 @@ class Op(C.Structure):
 class Config(C.Structure):
     _fields_ = [("atom_duration_us", C.c_double), ("max_outstanding", C.c_int32),
                 ("max_outstanding_hp", C.c_int32), ("steal", C.c_int32), ("atomize", C.c_int32),
-                ("xcd_remap", C.c_int32), ("prelude", C.c_int32), ("ema_alpha", C.c_double)]
+                ("xcd_remap", C.c_int32), ("prelude", C.c_int32), ("ema_alpha", C.c_double),
+                ("rightsize_slip", C.c_double)]
 
     @classmethod
     def default(cls, **kw):
-        c = cls(250.0, 2, 0, 1, 1, 1, 0, 0.25)
+        c = cls(250.0, 2, 0, 1, 1, 1, 0, 0.25, 0.0)
         for k, v in kw.items():
             setattr(c, k, v)
         return c
@@ -61,12 +62,12 @@ class RightsizeResult(C.Structure):
     _fields_ = [("n_points", C.c_int32), ("cus", C.c_int32 * MAX_SWEEP), ("median_us", C.c_double * MAX_SWEEP),
                 ("chosen_cus", C.c_int32), ("chosen_us", C.c_double), ("full_us", C.c_double),
                 ("occupancy_bound_cus", C.c_int32), ("model_m", C.c_double), ("model_b", C.c_double),
-                ("model_cus", C.c_int32)]
+                ("model_cus", C.c_int32), ("online_cus", C.c_int32)]
 
 
 class Stats(C.Structure):
     _fields_ = [("kernels", C.c_uint64), ("atoms", C.c_uint64), ("stolen_atoms", C.c_uint64),
-                ("revocations", C.c_uint64), ("predictions", C.c_uint64), ("mispredicts", C.c_uint64), ("abs_err_sum_us", C.c_double)]
+                ("revocations", C.c_uint64), ("rightsized_kernels", C.c_uint64), ("predictions", C.c_uint64), ("mispredicts", C.c_uint64), ("abs_err_sum_us", C.c_double)]
 
 
 class CoreAtom(C.Structure):

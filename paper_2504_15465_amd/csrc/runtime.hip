@@ -187,6 +187,7 @@ void default_config(lithos_config_t* c)
     c->xcd_remap = 1;
     c->prelude = 0;
     c->ema_alpha = 0.25;
+    c->rightsize_slip = 0.0;
 }
 
 void retire_stream(lithos_ctx* ctx, hipStream_t s)
@@ -228,6 +229,10 @@ int lithos_init(int device, const lithos_config_t* cfg, lithos_ctx_t** out)
         if (ctx->cfg.atom_duration_us <= 0) ctx->cfg.atom_duration_us = 250.0;
         if (ctx->cfg.max_outstanding <= 0) ctx->cfg.max_outstanding = 2;
         if (ctx->cfg.ema_alpha <= 0 || ctx->cfg.ema_alpha > 1) ctx->cfg.ema_alpha = 0.25;
+        if (ctx->cfg.rightsize_slip != 0.0 && !(ctx->cfg.rightsize_slip >= 1.0)) {
+            delete ctx;
+            return fail(LITHOS_EINVAL, "lithos_init: rightsize_slip must be 0 (off) or >= 1");
+        }
     }
     hipDeviceProp_t prop;
     hipError_t e = hipGetDeviceProperties(&prop, device);
@@ -646,6 +651,9 @@ int lithos_rightsize(lithos_ctx_t* ctx, const lithos_op_t* op, int cu_lo, int cu
         for (int t = 1; t <= out->cus[last]; ++t)
             if (out->model_m / t + out->model_b <= target * (1 + 1e-12)) { out->model_cus = t; break; }
     }
+    // Section 4.5 'Operation': the occupancy bound if the kernel cannot fill the allocation, else the model
+    out->online_cus = out->occupancy_bound_cus < out->cus[last] ? out->occupancy_bound_cus
+                                                                 : (last >= 1 ? out->model_cus : out->cus[last]);
     return LITHOS_OK;
 }
 

@@ -24,6 +24,16 @@ bool Predictor::us_per_block(int ordinal, int cus, double* out) const
     return true;
 }
 
+bool Predictor::measured(int ordinal, int cus, double* out) const
+{
+    auto row = table_.find(ordinal);
+    if (row == table_.end()) return false;
+    auto hit = row->second.find(cus);
+    if (hit == row->second.end()) return false;
+    *out = hit->second;
+    return true;
+}
+
 void Predictor::update(int ordinal, int cus, uint32_t blocks, double measured_us)
 {
     double v = measured_us / (double)blocks;
@@ -103,6 +113,27 @@ uint32_t Core::choose_mask(int tenant, double now_us, bool* stolen) const
     return mask;
 }
 
+// Section 4.5 'Operation' on the two CU sets a kernel can get right now (its quota, or the quota
+// plus borrowed CUs): true = the wider set is not worth taking.
+bool Core::keep_quota(const CoreTenant& t, const CoreKernel& k, int own_cus, int wide_cus) const
+{
+    // 'Filtering Outliers': CUs the kernel can fill = blocks / resident blocks per CU
+    const uint64_t bound = std::max<uint64_t>(1, ((uint64_t)k.total + k.wg_per_cu - 1) / k.wg_per_cu);
+    if (bound < (uint64_t)wide_cus) return bound <= (uint64_t)own_cus;
+    // 'Modeling Kernel Scaling': l = m/t + b through the kernel's latencies on the two sets
+    // (the model needs the kernel's latency on both sets: the wider one is measured first, then the
+    // quota once, after which the fit decides)
+    double u1, u2;
+    if (!t.predictor.measured(k.ordinal, wide_cus, &u2)) return false;
+    if (!t.predictor.measured(k.ordinal, own_cus, &u1)) return true;
+    const double l1 = u1 * k.total, l2 = u2 * k.total;
+    const double m = (l1 - l2) / (1.0 / own_cus - 1.0 / wide_cus), b = l2 - m / wide_cus;
+    const double target = cfg_.rightsize_slip * (m / wide_cus + b) * (1 + 1e-12);
+    for (int c = 1; c <= own_cus; ++c)
+        if (m / c + b <= target) return true;       // the minimum CU count within the slip fits in the quota
+    return false;
+}
+
 static uint32_t atom_count(double predicted_us, double atom_us, uint32_t total)
 {
     double n = predicted_us > 0 ? std::ceil(predicted_us / atom_us) : 1.0;
@@ -140,7 +171,13 @@ bool Core::next_atom(int ti, double now_us, lithos_core_atom_t* out)
     }
     const CoreKernel& k = t.cur;
     bool stolen = false;
-    const uint32_t mask = choose_mask(ti, now_us, &stolen);
+    uint32_t mask = choose_mask(ti, now_us, &stolen);
+    if (t.next_block == 0) {
+        // decided once per kernel; its atoms inherit the allocation (Section 4.5)
+        t.cur_narrow = stolen && cfg_.rightsize_slip >= 1.0 && keep_quota(t, k, cus_of(t.quota), cus_of(mask));
+        if (t.cur_narrow) t.stats.rightsized_kernels++;
+    }
+    if (t.cur_narrow) { mask = t.quota; stolen = false; }
     const int cus = cus_of(mask);
     const uint32_t remaining = k.total - t.next_block;
     uint32_t blocks = remaining;
@@ -201,6 +238,7 @@ lithos_stats_t Core::totals() const
         s.atoms += t.stats.atoms;
         s.stolen_atoms += t.stats.stolen_atoms;
         s.revocations += t.stats.revocations;
+        s.rightsized_kernels += t.stats.rightsized_kernels;
         s.predictions += t.stats.predictions;
         s.mispredicts += t.stats.mispredicts;
         s.abs_err_sum_us += t.stats.abs_err_sum_us;
@@ -248,7 +286,8 @@ int lithos_core_create(const lithos_config_t* cfg, int n_groups, int cus_per_gro
     lithos_config_t c;
     lithos::default_config(&c);
     if (cfg) c = *cfg;
-    if (c.atom_duration_us <= 0 || c.max_outstanding <= 0 || c.ema_alpha <= 0 || c.ema_alpha > 1)
+    if (c.atom_duration_us <= 0 || c.max_outstanding <= 0 || c.ema_alpha <= 0 || c.ema_alpha > 1 ||
+        (c.rightsize_slip != 0.0 && !(c.rightsize_slip >= 1.0)))
         return lithos::fail(LITHOS_EINVAL, "lithos_core_create: bad configuration");
     auto* h = new lithos_core();
     h->core = new lithos::Core(c, std::vector<int>(n_groups, cus_per_group));

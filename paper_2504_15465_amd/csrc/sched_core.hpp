@@ -23,6 +23,7 @@ class Predictor {
 public:
     explicit Predictor(double alpha) : alpha_(alpha) {}
     bool us_per_block(int ordinal, int cus, double* out) const;
+    bool measured(int ordinal, int cus, double* out) const;     // an entry of exactly this CU count
     void update(int ordinal, int cus, uint32_t blocks, double measured_us);
 private:
     double alpha_;
@@ -48,6 +49,7 @@ struct CoreTenant {
     int outstanding = 0;
     int queued_kernels = 0;             // kernels (not sync marks) in `queue`
     uint32_t prev_mask = 0;             // groups of the current kernel's previous atom (0: none launched yet)
+    bool cur_narrow = false;            // Section 4.5: the current kernel stays on the quota
     Predictor predictor;
     lithos_stats_t stats{};
     explicit CoreTenant(double alpha) : predictor(alpha) {}
@@ -87,6 +89,7 @@ public:
 
 private:
     uint32_t choose_mask(int tenant, double now_us, bool* stolen) const;
+    bool keep_quota(const CoreTenant& t, const CoreKernel& k, int own_cus, int wide_cus) const;
     lithos_config_t cfg_;
     std::vector<int> group_cus_;
     std::vector<CoreTenant> tenants_;

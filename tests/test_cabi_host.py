@@ -47,9 +47,9 @@ def test_binding_struct_sizes_match_the_header_layout():
     import ctypes as C
     assert C.sizeof(B.Op) == 4 * 4 + 8 * 8 + 4 * 8 + 4 * 4 + 6 * 8 + 2 * 8
     assert C.sizeof(B.Dim3) == 12
-    assert C.sizeof(B.Config) == 40
+    assert C.sizeof(B.Config) == 48
     assert C.sizeof(B.CoreAtom) == 56
-    assert C.sizeof(B.Stats) == 56
+    assert C.sizeof(B.Stats) == 64
 
 
 def test_core_rejects_bad_arguments():
@@ -81,7 +81,9 @@ BE_Q = frozenset(range(8, 32))
 
 
 def _lat(op, cus, blocks):
-    per_block = {"be": 62.5, "hp_a": 20.0, "hp_b": 24.0}[op]
+    if op == "be_flat":                        # a kernel that does not scale with CUs (per-block serial work)
+        return 2.0 + 0.4 * blocks
+    per_block = {"be": 62.5, "hp_a": 20.0, "hp_b": 24.0, "be_small": 300.0}[op]
     return 2.0 + per_block * blocks / cus
 
 
@@ -277,3 +279,71 @@ def test_policy_core_matches_oracle_model_with_three_tenants(atomize, steal):
         assert sim_ids[2] in stolen_by                      # best effort lives on lent CUs
         assert any(g[5] and g[0] in sim_ids[:2] for g in got)   # a high-priority tenant borrowed too
     B.lithos_core_destroy(h.c)
+
+
+@pytest.mark.parametrize("slip", [1.1, 1.5])
+def test_policy_core_right_sizes_online_like_the_oracle_model(slip):
+    """Section 4.5 'Operation' in the dispatcher: a best-effort tenant whose kernels could borrow the idle
+    high-priority CUs borrows them only when the occupancy filter and the two-point model say the wider
+    set pays.  Three kinds of best-effort kernel per batch: one that scales (1024 blocks), one that does
+    not (constant latency per block count), one too small to fill more than the quota (96 blocks)."""
+    rnd = random.Random(11)
+    scenario = []
+    for i in range(60):
+        for total, op in ((1024, "be"), (512, "be_flat"), (96, "be_small")):
+            scenario.append((0.0, "submit", "be", total, op))
+        scenario.append((0.0, "sync", "be", 0, ""))
+    for t in sorted(rnd.uniform(100, 60000) for _ in range(25)):
+        scenario.append((t, "submit", "hp", 64, "hp_a"))
+        scenario.append((t, "sync", "hp", 0, ""))
+
+    sim = Simulator(SimConfig(atom_duration_us=100.0, max_outstanding=2, rightsize_slip=slip), _lat)
+    hp, be = sim.add_tenant(HP_Q, hp=True), sim.add_tenant(BE_Q, hp=False)
+    for time, kind, who, total, op in scenario:
+        tid = hp if who == "hp" else be
+        if kind == "submit":
+            sim.submit_at(time, tid, Kernel(op, total, 1))
+        else:
+            sim.sync_at(time, tid)
+    sim.run()
+    want = [(a.tenant, a.ordinal, a.lo, a.hi, _bits(a.mask), a.stolen, a.t_start, a.t_end) for a in sim.trace]
+
+    h = CoreHarness(B.Config.default(atom_duration_us=100.0, max_outstanding=2, rightsize_slip=slip), {})
+    for time, kind, who, total, op in scenario:
+        tid = h.hp if who == "hp" else h.be
+        if kind == "submit":
+            h.push(time, "submit", (tid, total, op))
+        else:
+            h.push(time, "sync", tid)
+    h.run()
+    got = [(t, o, lo, hi, m, st, s, e) for t, o, lo, hi, m, st, _, s, e in h.trace]
+    assert len(got) == len(want)
+    for g, w in zip(got, want):
+        assert g[:6] == w[:6], (g, w)
+        assert abs(g[6] - w[6]) < 1e-9 and abs(g[7] - w[7]) < 1e-9
+    st = B.lithos_core_stats(h.c, h.be)
+    book = sim.per_tenant[be]
+    assert (st.atoms, st.stolen_atoms, st.revocations, st.rightsized_kernels) == \
+        (book["atoms"], book["steals"], book["revocations"], book["rightsized"])
+    # once the best-effort queue has drained, the high-priority kernels (64 blocks = its 64 CUs) could
+    # borrow and the occupancy filter keeps them at home: the same count on both sides
+    assert B.lithos_core_stats(h.c, h.hp).rightsized_kernels == sim.per_tenant[hp]["rightsized"]
+    assert all(g[4] == _bits(HP_Q) for g in got if g[0] == h.hp)
+    own = _bits(BE_Q)
+    small = [g for g in got if g[0] == h.be and g[1] == 2]
+    assert small and all(g[4] == own for g in small)                  # 96 blocks cannot fill more than 192 CUs: never borrows
+    flat = [g for g in got if g[0] == h.be and g[1] == 1]
+    assert any(g[4] != own for g in flat[:6])                          # borrows until both CU sets have been measured ...
+    assert all(g[4] == own for g in flat[-20:])                        # ... then the model says the wider set gains nothing
+    scal = [g for g in got if g[0] == h.be and g[1] == 0]
+    if slip == 1.1:
+        assert any(g[4] != own for g in scal[-20:])                    # 256 vs 192 CUs is a 1.33x gain: worth borrowing at k = 1.1
+    else:
+        assert all(g[4] == own for g in scal[-20:])                    # but inside a slip of 1.5
+    B.lithos_core_destroy(h.c)
+
+
+def test_core_refuses_a_slip_below_one():
+    with pytest.raises(B.LithosError) as e:
+        B.lithos_core_create(B.Config.default(rightsize_slip=0.5), 32, 8)
+    assert e.value.code == B.EINVAL

@@ -82,6 +82,14 @@ def test_rightsize_sweep_on_a_spin_kernel_and_selection_rule():
     assert r.occupancy_bound_cus == 256
     m, b = r.model_m, r.model_b
     assert abs(m / cus[0] + b - lat[0]) < 1e-6 * lat[0] and abs(m / cus[-1] + b - lat[-1]) < 1e-6 * lat[-1]
+    # the model's pick is the oracle's, from the oracle's own fit through the measured end points
+    mo, bo = R.fit_through(cus[0], lat[0], cus[-1], lat[-1])
+    assert abs(mo - m) <= 1e-9 * abs(m) and abs(bo - b) <= 1e-6 * max(1.0, abs(b))
+    assert r.model_cus == R.min_units_for_slip(mo, bo, cus[-1], 1.04)
+    assert r.online_cus == r.model_cus                  # the kernel can fill all 256 CUs: the model decides
+    small = B.lithos_rightsize(c, B.spin_op(64, 5000), 32, 256, 32, 1, 3, 0.04)
+    assert small.occupancy_bound_cus == R.occupancy_bound(64, 2) == 32
+    assert small.online_cus == 32                       # 64 blocks, two per CU: the occupancy filter decides
     with pytest.raises(B.LithosError):
         B.lithos_rightsize(c, op, 8, 512, 8, 1, 3, 0.04)
 

@@ -240,3 +240,38 @@ def test_three_tenants_bit_exact_with_stealing_between_all_of_them():
         assert st[2].stolen_atoms > 0 and st[2].atoms > st[2].kernels
     finally:
         drop_world(c, parts, ts)
+
+
+def test_online_right_sizing_borrows_only_when_it_pays():
+    """Section 4.5 'Operation' in the dispatcher.  A tenant with a 64-CU quota beside an idle tenant that
+    owns 192: a kernel that cannot fill more than 64 CUs never borrows (occupancy filter); a kernel that
+    scales borrows, after one run on each CU set has given the model its two points."""
+    cfg = B.Config.default(atom_duration_us=1e6, max_outstanding=2, steal=1, atomize=1, rightsize_slip=1.1)
+    c, p_a, p_b = make_world(cfg)
+    t_a = B.lithos_tenant_create(c, B.CLASS_BE, p_a)       # 64 CUs
+    t_b = B.lithos_tenant_create(c, B.CLASS_HP, p_b)       # 192 CUs, never submits
+    try:
+        small = B.spin_op(128, 2000)                        # two blocks per CU: fills exactly 64 CUs
+        for _ in range(4):
+            B.lithos_submit(t_a, small)
+            B.lithos_sync(t_a)
+        s = B.lithos_tenant_stats(t_a)
+        assert s.kernels == 4 and s.stolen_atoms == 0 and s.rightsized_kernels == 4
+        # the scaling kernel follows the small one in every batch, so it has its own ordinal (the
+        # predictor is keyed by a kernel's position since the last synchronisation, Section 4.7)
+        big = B.spin_op(4096, 4000)                         # 32 waves on 64 CUs, 8 on 256: scales
+        t = []
+        for _ in range(5):
+            t0 = time.perf_counter()
+            B.lithos_submit(t_a, small)
+            B.lithos_submit(t_a, big)
+            B.lithos_sync(t_a)
+            t.append(time.perf_counter() - t0)
+        s2 = B.lithos_tenant_stats(t_a)
+        assert s2.kernels - s.kernels == 10
+        assert s2.rightsized_kernels - s.rightsized_kernels == 5 + 1  # the small ones, and the one run that gave the second point
+        assert s2.stolen_atoms - s.stolen_atoms == 4                  # first run (nothing known) and the three after the fit
+        assert t[1] > 2.5 * t[0] and t[4] < 0.5 * t[1]                # 64 CUs take four times as long as 256
+        assert B.lithos_stats(c).rightsized_kernels == 10
+    finally:
+        drop_world(c, [p_a, p_b], [t_a, t_b])

@@ -173,3 +173,47 @@ def test_capacity_statistics():
     y = [3.0, 2.0, 1.0]
     assert rightsize.r_squared(y, y) == 1.0
     assert abs(rightsize.r_squared(y, [2.0, 2.0, 2.0])) < 1e-15
+
+
+def test_general_two_point_fit_and_the_online_rule():
+    """Section 4.5: the fit through any two allocations reduces to the (1, T) fit, passes through its
+    points, and recovers a known Amdahl curve; 'Operation' = occupancy filter first, model second."""
+    T = 108
+    m1, b1 = rightsize.fit_two_point(1000.0, 10.0, T)
+    m2, b2 = rightsize.fit_through(1, 1000.0, T, 10.0)
+    assert abs(m1 - m2) < 1e-9 and abs(b1 - b2) < 1e-9
+    m, b = 4000.0, 7.5                                    # l = 4000/t + 7.5 sampled at 64 and 256 units
+    mm, bb = rightsize.fit_through(64, m / 64 + b, 256, m / 256 + b)
+    assert abs(mm - m) < 1e-9 and abs(bb - b) < 1e-9
+    mm, bb = rightsize.fit_through(256, m / 256 + b, 64, m / 64 + b)          # order of the points is free
+    assert abs(mm - m) < 1e-9 and abs(bb - b) < 1e-9
+    with pytest.raises(ValueError):
+        rightsize.fit_through(64, 1.0, 64, 2.0)
+
+    cands = [64, 256]
+    lat = lambda t: m / t + b
+    # occupancy filter: 128 blocks, 2 per unit -> 64 units are all the kernel can fill
+    assert rightsize.online_choice(128, 2, 256, cands, {}, 1.1) == 64
+    assert rightsize.online_choice(130, 2, 256, cands, {}, 1.1) == 256        # bound 65 > 64: next set up
+    assert rightsize.online_choice(10 ** 6, 2, 256, cands, {}, 1.1) == 256    # model unknown: keep the allocation
+    assert rightsize.online_choice(10 ** 6, 2, 256, cands, {256: lat(256)}, 1.1) == 64    # second point: run there once
+    assert rightsize.online_choice(10 ** 6, 2, 256, cands, {64: lat(64)}, 1.1) == 256     # the allocation first
+    assert rightsize.online_choice(10 ** 6, 2, 256, [256], {256: lat(256)}, 1.1) == 256   # nothing narrower on offer
+    # model: l(256) = 23.125; k = 1.1 needs 4000/t + 7.5 <= 25.44 -> t >= 223 -> 256;
+    # k = 3.0 needs 4000/t <= 61.9 -> t >= 65 -> 256; k = 3.1 -> t >= 63 -> 64
+    known = {64: lat(64), 256: lat(256)}
+    assert rightsize.online_choice(10 ** 6, 2, 256, cands, known, 1.1) == 256
+    assert rightsize.online_choice(10 ** 6, 2, 256, cands, known, 3.0) == 256
+    assert rightsize.online_choice(10 ** 6, 2, 256, cands, known, 3.1) == 64
+    # a kernel that does not scale (constant latency): one unit would do, the smallest set wins at any k
+    assert rightsize.online_choice(10 ** 6, 2, 256, cands, {64: 50.0, 256: 50.0}, 1.0) == 64
+    # brute force: the choice is the smallest candidate whose model latency is within the slip
+    for k in (1.0, 1.05, 1.1, 1.5, 2.0, 4.0):
+        for mb in ((100.0, 1.0), (5000.0, 0.0), (10.0, 40.0)):
+            f = lambda t: mb[0] / t + mb[1]
+            c3 = [64, 128, 192, 256]
+            got = rightsize.online_choice(10 ** 6, 1, 256, c3, {64: f(64), 256: f(256)}, k)
+            want = min(c for c in c3 if min(t for t in range(1, 257) if f(t) <= k * f(256) * (1 + 1e-12)) <= c)
+            assert got == want, (k, mb, got, want)
+    with pytest.raises(ValueError):
+        rightsize.online_choice(10, 1, 128, cands, {}, 1.1)                    # allocation is not a candidate
