@@ -275,6 +275,51 @@ int lo_attention(int64_t Bn, int64_t Hq, int64_t Hkv, int64_t Sq, int64_t Sk, in
     return 0;
 }
 
+/* Causal self-attention over a prompt: query i (0-based, Sq == Sk positions)
+ * sees keys 0..i only:
+ *   O[b,i,h,:] = sum_{j<=i} softmax_{j<=i}( Q[b,i,h,:] . K[b,j,g,:] * scale ) V[b,j,g,:]
+ * Same layout and grouped-query rule as lo_attention. */
+int lo_attention_causal(int64_t Bn, int64_t Hq, int64_t Hkv, int64_t S, int64_t d,
+                        const double *Q, int64_t qb, int64_t qt, int64_t qh,
+                        const double *Kx, int64_t kb, int64_t kt, int64_t kh,
+                        const double *V, int64_t vb, int64_t vt, int64_t vh,
+                        double scale,
+                        double *O, int64_t ob, int64_t ot, int64_t oh)
+{
+    if (Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || d <= 0) return -1;
+    int64_t group = Hq / Hkv;
+    int64_t work = Bn * Hq * S;
+#pragma omp parallel
+    {
+        double *p = (double *)__builtin_malloc((size_t)S * sizeof(double));
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t w = 0; w < work; ++w) {
+            int64_t b = w / (Hq * S), h = (w / S) % Hq, i = w % S;
+            int64_t g = h / group;
+            const double *q = Q + b * qb + i * qt + h * qh;
+            double mx = -INFINITY;
+            for (int64_t j = 0; j <= i; ++j) {
+                const double *kk = Kx + b * kb + j * kt + g * kh;
+                double s = 0.0;
+                for (int64_t e = 0; e < d; ++e) s += q[e] * kk[e];
+                p[j] = s * scale;
+                if (p[j] > mx) mx = p[j];
+            }
+            double den = 0.0;
+            for (int64_t j = 0; j <= i; ++j) { p[j] = exp(p[j] - mx); den += p[j]; }
+            double *o = O + b * ob + i * ot + h * oh;
+            for (int64_t e = 0; e < d; ++e) {
+                double acc = 0.0;
+                for (int64_t j = 0; j <= i; ++j)
+                    acc += (p[j] / den) * V[b * vb + j * vt + g * vh + e];
+                o[e] = acc;
+            }
+        }
+        __builtin_free(p);
+    }
+    return 0;
+}
+
 /* ---------------------------------------------------- rotary embedding --- */
 
 /* Rotate-half pairing on a head of even width d: element e < d/2 is paired

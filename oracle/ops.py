@@ -237,6 +237,32 @@ def attention(q, k, v, scale: float) -> np.ndarray:
     return o
 
 
+def attention_causal(q, k, v, scale: float) -> np.ndarray:
+    """Causal self-attention over a prompt: q [B,S,Hq,d], k/v [B,S,Hkv,d] -> o [B,S,Hq,d] fp64;
+    query i sees keys 0..i.  Grouped-query rule as in ``attention``."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    Bn, S, Hq, d = q.shape
+    if k.shape != v.shape or k.shape[0] != Bn or k.shape[1] != S or k.shape[3] != d:
+        raise ValueError("attention operand shapes")
+    Hkv = k.shape[2]
+    for t in (q, k, v):
+        if t.strides[-1] != 8:
+            raise ValueError("innermost dimension must be contiguous")
+    o = np.empty((Bn, S, Hq, d), dtype=np.float64)
+
+    def st(t):
+        return [_i64(t.strides[0] // 8), _i64(t.strides[1] // 8), _i64(t.strides[2] // 8)]
+
+    rc = lib().lo_attention_causal(_i64(Bn), _i64(Hq), _i64(Hkv), _i64(S), _i64(d),
+                                   q.ctypes.data_as(_pd), *st(q), k.ctypes.data_as(_pd), *st(k),
+                                   v.ctypes.data_as(_pd), *st(v), _dbl(scale), o.ctypes.data_as(_pd), *st(o))
+    if rc != 0:
+        raise ValueError("lo_attention_causal rejected its arguments")
+    return o
+
+
 def rope(x, pos, theta: float = 10000.0) -> np.ndarray:
     """x [rows, heads, d]; pos [rows] int; rotate-half pairing."""
     a, pa = _d(x)

@@ -397,6 +397,26 @@ static attn_fn dec_fn(int G, bool q32, bool o32)
 #undef PICKG
 }
 
+// the kernel that serves a (validated) descriptor
+static attn_fn attn_kernel(const lithos_op_t& op)
+{
+    if (op.kind == LITHOS_OP_ATTN_ENC)
+        return op.dim[2] == 64 ? (attn_fn)attn_enc_kernel<2> : op.dim[2] == 128 ? (attn_fn)attn_enc_kernel<4> : (attn_fn)attn_enc_kernel<8>;
+    const int G = (int)(op.dim[1] / op.dim[2]);
+    const bool o32 = op.flags & LITHOS_F_OUT_F32;
+    if (op.kind == LITHOS_OP_ATTN_MERGE)
+        return G == 1 ? (o32 ? (attn_fn)attn_merge_kernel<1, true> : (attn_fn)attn_merge_kernel<1, false>)
+             : G == 2 ? (o32 ? (attn_fn)attn_merge_kernel<2, true> : (attn_fn)attn_merge_kernel<2, false>)
+                      : (o32 ? (attn_fn)attn_merge_kernel<4, true> : (attn_fn)attn_merge_kernel<4, false>);
+    return dec_fn(G, op.flags & LITHOS_F_IN_F32, o32);
+}
+
+// resident workgroups per CU, from the runtime (the constants are the fallback)
+static void attn_occupancy(const lithos_op_t& op, OpPlan* plan)
+{
+    plan->wg_per_cu = cached_occupancy((const void*)attn_kernel(op), (int)plan->threads, plan->wg_per_cu);
+}
+
 int attn_plan(const lithos_op_t& op, OpPlan* plan)
 {
     plan->threads = 256;
@@ -411,6 +431,7 @@ int attn_plan(const lithos_op_t& op, OpPlan* plan)
         plan->grid = {(uint32_t)heads, (uint32_t)batch, 1};
         plan->total = (uint32_t)(batch * heads);
         plan->wg_per_cu = 2;
+        attn_occupancy(op, plan);
         return LITHOS_OK;
     }
     if (op.kind == LITHOS_OP_ATTN_MERGE) {
@@ -425,6 +446,7 @@ int attn_plan(const lithos_op_t& op, OpPlan* plan)
         plan->grid = {(uint32_t)n_kv, (uint32_t)batch, 1};
         plan->total = (uint32_t)(batch * n_kv);
         plan->wg_per_cu = 4;
+        attn_occupancy(op, plan);
         return LITHOS_OK;
     }
     // decode: dim = batch, n_q, n_kv, d, keys, cap, splits
@@ -445,6 +467,7 @@ int attn_plan(const lithos_op_t& op, OpPlan* plan)
     plan->grid = {(uint32_t)(n_kv * splits), (uint32_t)batch, 1};
     plan->total = (uint32_t)(batch * n_kv * splits);
     plan->wg_per_cu = 2;
+    attn_occupancy(op, plan);
     return LITHOS_OK;
 }
 
@@ -458,19 +481,13 @@ int attn_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     const dim3 grid(LITHOS_ATOM_LAUNCH_BLOCKS(atom)), block(256);
     if (op.kind == LITHOS_OP_ATTN_ENC) {
         a.batch = (int)op.dim[0]; a.n_q = (int)op.dim[1]; a.seq = (int)op.dim[2]; a.d = (int)op.dim[3];
-        attn_fn fn = a.seq == 64 ? (attn_fn)attn_enc_kernel<2> : a.seq == 128 ? (attn_fn)attn_enc_kernel<4> : (attn_fn)attn_enc_kernel<8>;
-        LITHOS_HIP(launch_kernel(fn, grid, block, s, a, atom));
+        LITHOS_HIP(launch_kernel(attn_kernel(op), grid, block, s, a, atom));
         return LITHOS_OK;
     }
     if (op.kind == LITHOS_OP_ATTN_MERGE) {
         a.batch = (int)op.dim[0]; a.n_q = (int)op.dim[1]; a.n_kv = (int)op.dim[2]; a.d = (int)op.dim[3]; a.splits = (int)op.dim[4];
         a.ws = (float*)const_cast<void*>(op.in[0]);
-        const int G = a.n_q / a.n_kv;
-        const bool o32 = op.flags & LITHOS_F_OUT_F32;
-        attn_fn fn = G == 1 ? (o32 ? (attn_fn)attn_merge_kernel<1, true> : (attn_fn)attn_merge_kernel<1, false>)
-                   : G == 2 ? (o32 ? (attn_fn)attn_merge_kernel<2, true> : (attn_fn)attn_merge_kernel<2, false>)
-                            : (o32 ? (attn_fn)attn_merge_kernel<4, true> : (attn_fn)attn_merge_kernel<4, false>);
-        LITHOS_HIP(launch_kernel(fn, grid, block, s, a, atom));
+        LITHOS_HIP(launch_kernel(attn_kernel(op), grid, block, s, a, atom));
         return LITHOS_OK;
     }
     a.k = (const uint16_t*)op.in[1];
@@ -480,8 +497,7 @@ int attn_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     a.batch = (int)op.dim[0]; a.n_q = (int)op.dim[1]; a.n_kv = (int)op.dim[2]; a.d = (int)op.dim[3];
     a.seq = (int)op.dim[4]; a.cap = (int)op.dim[5];
     a.ldq = op.ld[0];
-    attn_fn fn = dec_fn(a.n_q / a.n_kv, op.flags & LITHOS_F_IN_F32, op.flags & LITHOS_F_OUT_F32);
-    LITHOS_HIP(launch_kernel(fn, grid, block, s, a, atom));
+    LITHOS_HIP(launch_kernel(attn_kernel(op), grid, block, s, a, atom));
     return LITHOS_OK;
 }
 

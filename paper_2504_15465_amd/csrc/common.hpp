@@ -61,6 +61,10 @@ inline hipError_t launch_kernel(void (*k)(Params...), dim3 grid, dim3 block, hip
     return hipLaunchKernel(reinterpret_cast<const void*>(k), grid, block, ptrs, 0, s);
 }
 
+// hipOccupancyMaxActiveBlocksPerMultiprocessor for a kernel and workgroup size (no dynamic LDS), asked
+// once per (device, kernel, size) and remembered; `fallback` if the runtime cannot say.
+uint32_t cached_occupancy(const void* kernel, int threads, uint32_t fallback);
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 } // namespace lithos

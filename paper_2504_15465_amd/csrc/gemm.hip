@@ -110,10 +110,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
     plan->total = plan->grid.x * plan->grid.y * plan->grid.z;
     plan->threads = tile_threads(variant);
     plan->variant = variant;
-    int occ = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void*)variant_fn(variant, ta, tb, a32, split, staged_epilogue(op)), tile_threads(variant), 0);
-    plan->wg_per_cu = (e == hipSuccess && occ > 0) ? (uint32_t)occ : 1u;
-    if (e != hipSuccess) (void)hipGetLastError();
+    plan->wg_per_cu = cached_occupancy((const void*)variant_fn(variant, ta, tb, a32, split, staged_epilogue(op)), tile_threads(variant), 1);
     return LITHOS_OK;
 }
 

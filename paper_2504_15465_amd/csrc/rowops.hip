@@ -461,6 +461,34 @@ static RowArgs make_args(const lithos_op_t& op)
 
 static int tpr_for(int64_t cols) { return cols <= 1024 ? 64 : 256; }
 
+// The kernel that serves a descriptor (everything but SPIN, whose kernel has its own signature).
+typedef void (*row_fn)(RowArgs, AtomArgs);
+#define PICK2(K) (in32 ? (out32 ? (row_fn)K<true, true> : (row_fn)K<true, false>) : (out32 ? (row_fn)K<false, true> : (row_fn)K<false, false>))
+#define PICK3(K, T) (in32 ? (out32 ? (row_fn)K<true, true, T> : (row_fn)K<true, false, T>) : (out32 ? (row_fn)K<false, true, T> : (row_fn)K<false, false, T>))
+static row_fn row_kernel(const lithos_op_t& op, int variant)
+{
+    const bool in32 = op.flags & LITHOS_F_IN_F32, out32 = op.flags & LITHOS_F_OUT_F32;
+    const bool wide = tpr_for(op.dim[1]) == 256;
+    switch (op.kind) {
+    case LITHOS_OP_BIAS_ACT: return PICK2(bias_act_kernel);
+    case LITHOS_OP_SILU_MUL: return PICK2(silu_mul_kernel);
+    case LITHOS_OP_SUM_SLICES:
+        return variant == 1 ? (out32 ? (row_fn)sum_slices_kernel<true, true> : (row_fn)sum_slices_kernel<false, true>)
+                            : (out32 ? (row_fn)sum_slices_kernel<true, false> : (row_fn)sum_slices_kernel<false, false>);
+    case LITHOS_OP_LAYERNORM:
+        if (variant == 1) return wide ? PICK3(layernorm_vec_kernel, 256) : PICK3(layernorm_vec_kernel, 64);   // register-resident rows
+        return wide ? PICK3(layernorm_kernel, 256) : PICK3(layernorm_kernel, 64);
+    case LITHOS_OP_RMSNORM:
+        if (variant == 1) return wide ? PICK3(rmsnorm_vec_kernel, 256) : PICK3(rmsnorm_vec_kernel, 64);
+        return wide ? PICK3(rmsnorm_kernel, 256) : PICK3(rmsnorm_kernel, 64);
+    case LITHOS_OP_SOFTMAX: return wide ? PICK3(softmax_kernel, 256) : PICK3(softmax_kernel, 64);
+    case LITHOS_OP_ROPE_KV: return in32 ? (row_fn)rope_kv_kernel<true> : (row_fn)rope_kv_kernel<false>;
+    default: return nullptr;
+    }
+}
+#undef PICK2
+#undef PICK3
+
 int rowops_plan(const lithos_op_t& op, OpPlan* plan)
 {
     const int64_t rows = op.dim[0], cols = op.dim[1];
@@ -535,91 +563,32 @@ int rowops_plan(const lithos_op_t& op, OpPlan* plan)
     if (blocks == 0 || blocks > 0x7fffffffull) return fail(LITHOS_EINVAL, "row op %d: grid out of range", op.kind);
     plan->grid = {(uint32_t)blocks, 1, 1};
     plan->total = (uint32_t)blocks;
+    // resident workgroups per CU: asked of the runtime once per kernel (it feeds the atom quantum and
+    // the occupancy filter of right-sizing); the constants above only serve if the query fails
+    const void* fn = op.kind == LITHOS_OP_SPIN ? (const void*)spin_kernel : (const void*)row_kernel(op, plan->variant);
+    plan->wg_per_cu = cached_occupancy(fn, (int)plan->threads, plan->wg_per_cu);
     return LITHOS_OK;
 }
 
 int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, hipStream_t s)
 {
-    RowArgs a = make_args(op);
-    const bool in32 = op.flags & LITHOS_F_IN_F32, out32 = op.flags & LITHOS_F_OUT_F32;
     const dim3 grid(LITHOS_ATOM_LAUNCH_BLOCKS(atom)), block(plan.threads);
-    hipError_t e = hipSuccess;
-#define L2(K, A, B) e = launch_kernel(K<A, B>, grid, block, s, a, atom)
-#define L3(K, A, B, C) e = launch_kernel(K<A, B, C>, grid, block, s, a, atom)
-    switch (op.kind) {
-    case LITHOS_OP_BIAS_ACT:
-        if (in32) { if (out32) L2(bias_act_kernel, true, true); else L2(bias_act_kernel, true, false); }
-        else      { if (out32) L2(bias_act_kernel, false, true); else L2(bias_act_kernel, false, false); }
-        break;
-    case LITHOS_OP_SILU_MUL:
-        if (in32) { if (out32) L2(silu_mul_kernel, true, true); else L2(silu_mul_kernel, true, false); }
-        else      { if (out32) L2(silu_mul_kernel, false, true); else L2(silu_mul_kernel, false, false); }
-        break;
-    case LITHOS_OP_SUM_SLICES:
+    if (op.kind == LITHOS_OP_SPIN) {
+        LITHOS_HIP(launch_kernel(spin_kernel, grid, block, s, (uint64_t)op.dim[1], atom));
+        return LITHOS_OK;
+    }
+    RowArgs a = make_args(op);
+    if (op.kind == LITHOS_OP_SUM_SLICES) {
         a.aux[0] = op.dim[2]; a.aux[1] = op.dim[3]; a.aux[2] = op.ld[0]; a.aux[3] = op.ld[1];
         a.aux[4] = op.ld[2];
-        if (plan.variant == 1) { if (out32) L2(sum_slices_kernel, true, true); else L2(sum_slices_kernel, false, true); }
-        else                   { if (out32) L2(sum_slices_kernel, true, false); else L2(sum_slices_kernel, false, false); }
-        break;
-    case LITHOS_OP_LAYERNORM:
-        if (plan.variant == 1) {          // register-resident rows
-            if (tpr_for(a.cols) == 64) {
-                if (in32) { if (out32) L3(layernorm_vec_kernel, true, true, 64); else L3(layernorm_vec_kernel, true, false, 64); }
-                else      { if (out32) L3(layernorm_vec_kernel, false, true, 64); else L3(layernorm_vec_kernel, false, false, 64); }
-            } else {
-                if (in32) { if (out32) L3(layernorm_vec_kernel, true, true, 256); else L3(layernorm_vec_kernel, true, false, 256); }
-                else      { if (out32) L3(layernorm_vec_kernel, false, true, 256); else L3(layernorm_vec_kernel, false, false, 256); }
-            }
-        } else if (tpr_for(a.cols) == 64) {
-            if (in32) { if (out32) L3(layernorm_kernel, true, true, 64); else L3(layernorm_kernel, true, false, 64); }
-            else      { if (out32) L3(layernorm_kernel, false, true, 64); else L3(layernorm_kernel, false, false, 64); }
-        } else {
-            if (in32) { if (out32) L3(layernorm_kernel, true, true, 256); else L3(layernorm_kernel, true, false, 256); }
-            else      { if (out32) L3(layernorm_kernel, false, true, 256); else L3(layernorm_kernel, false, false, 256); }
-        }
-        break;
-    case LITHOS_OP_RMSNORM:
-        if (plan.variant == 1) {          // register-resident rows
-            if (tpr_for(a.cols) == 64) {
-                if (in32) { if (out32) L3(rmsnorm_vec_kernel, true, true, 64); else L3(rmsnorm_vec_kernel, true, false, 64); }
-                else      { if (out32) L3(rmsnorm_vec_kernel, false, true, 64); else L3(rmsnorm_vec_kernel, false, false, 64); }
-            } else {
-                if (in32) { if (out32) L3(rmsnorm_vec_kernel, true, true, 256); else L3(rmsnorm_vec_kernel, true, false, 256); }
-                else      { if (out32) L3(rmsnorm_vec_kernel, false, true, 256); else L3(rmsnorm_vec_kernel, false, false, 256); }
-            }
-        } else if (tpr_for(a.cols) == 64) {
-            if (in32) { if (out32) L3(rmsnorm_kernel, true, true, 64); else L3(rmsnorm_kernel, true, false, 64); }
-            else      { if (out32) L3(rmsnorm_kernel, false, true, 64); else L3(rmsnorm_kernel, false, false, 64); }
-        } else {
-            if (in32) { if (out32) L3(rmsnorm_kernel, true, true, 256); else L3(rmsnorm_kernel, true, false, 256); }
-            else      { if (out32) L3(rmsnorm_kernel, false, true, 256); else L3(rmsnorm_kernel, false, false, 256); }
-        }
-        break;
-    case LITHOS_OP_SOFTMAX:
-        if (tpr_for(a.cols) == 64) {
-            if (in32) { if (out32) L3(softmax_kernel, true, true, 64); else L3(softmax_kernel, true, false, 64); }
-            else      { if (out32) L3(softmax_kernel, false, true, 64); else L3(softmax_kernel, false, false, 64); }
-        } else {
-            if (in32) { if (out32) L3(softmax_kernel, true, true, 256); else L3(softmax_kernel, true, false, 256); }
-            else      { if (out32) L3(softmax_kernel, false, true, 256); else L3(softmax_kernel, false, false, 256); }
-        }
-        break;
-    case LITHOS_OP_ROPE_KV:
+    } else if (op.kind == LITHOS_OP_ROPE_KV) {
         a.cols = op.dim[3];
         a.aux[0] = op.dim[1]; a.aux[1] = op.dim[2]; a.aux[2] = op.dim[4]; a.aux[3] = op.dim[5];
         a.p0 = nullptr; a.p1 = nullptr;
-        if (in32) e = launch_kernel(rope_kv_kernel<true>, grid, block, s, a, atom);
-        else e = launch_kernel(rope_kv_kernel<false>, grid, block, s, a, atom);
-        break;
-    case LITHOS_OP_SPIN:
-        e = launch_kernel(spin_kernel, grid, block, s, (uint64_t)op.dim[1], atom);
-        break;
-    default:
-        return fail(LITHOS_EINVAL, "unknown row op kind %d", op.kind);
     }
-#undef L2
-#undef L3
-    LITHOS_HIP(e);
+    row_fn fn = row_kernel(op, plan.variant);
+    if (!fn) return fail(LITHOS_EINVAL, "unknown row op kind %d", op.kind);
+    LITHOS_HIP(launch_kernel(fn, grid, block, s, a, atom));
     return LITHOS_OK;
 }
 

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <fstream>
+#include <map>
 #include <sstream>
 #include <vector>
 
@@ -51,6 +52,26 @@ static int static_scratch_setup(int device)
     if (e != hipSuccess || !p) return fail(LITHOS_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", device, hipGetErrorString(e));
     g_scratch_ptr[device] = static_cast<float*>(p);
     return LITHOS_OK;
+}
+
+uint32_t cached_occupancy(const void* kernel, int threads, uint32_t fallback)
+{
+    struct Key { int dev; const void* fn; int threads; bool operator<(const Key& o) const { return std::tie(dev, fn, threads) < std::tie(o.dev, o.fn, o.threads); } };
+    static std::mutex mu;
+    static std::map<Key, uint32_t> cache;
+    if (!kernel) return fallback ? fallback : 1u;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const Key key{dev, kernel, threads};
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = cache.find(key);
+    if (it != cache.end()) return it->second;
+    int occ = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, threads, 0);
+    if (e != hipSuccess) (void)hipGetLastError();
+    const uint32_t v = (e == hipSuccess && occ > 0) ? (uint32_t)occ : (fallback ? fallback : 1u);
+    cache[key] = v;
+    return v;
 }
 
 // ---- probe kernel: which die / CU does each workgroup run on ---------------

@@ -266,6 +266,35 @@ def test_attention_matches_torch_sdpa_and_gqa_expansion():
     assert np.array_equal(o1, o2)
 
 
+def test_causal_attention_is_attention_over_each_querys_prefix():
+    """Query i sees keys 0..i: equal to plain attention of that one query over the key prefix (brute force
+    over every query), to torch's causal SDPA, independent of later keys and values, and V[0] for query 0."""
+    rng = np.random.default_rng(12)
+    B, S, Hq, Hkv, d = 2, 11, 4, 2, 8
+    q = rng.standard_normal((B, S, Hq, d))
+    k = rng.standard_normal((B, S, Hkv, d))
+    v = rng.standard_normal((B, S, Hkv, d))
+    scale = 0.35
+    got = ops.attention_causal(q, k, v, scale)
+    for i in range(S):
+        want = ops.attention(q[:, i:i + 1], k[:, :i + 1], v[:, :i + 1], scale)
+        assert np.allclose(got[:, i:i + 1], want, atol=1e-14), i
+    g = Hq // Hkv
+    assert np.allclose(got[:, 0], np.repeat(v[:, 0], g, axis=1), atol=1e-15)           # one visible key
+    t = lambda a: torch.from_numpy(a).permute(0, 2, 1, 3)
+    ref = torch.nn.functional.scaled_dot_product_attention(t(q), t(np.repeat(k, g, axis=2)), t(np.repeat(v, g, axis=2)),
+                                                           is_causal=True, scale=scale)
+    assert np.allclose(got, ref.permute(0, 2, 1, 3).numpy(), atol=1e-12)
+    k2, v2 = k.copy(), v.copy()
+    k2[:, 7:] += 5.0
+    v2[:, 7:] -= 3.0
+    got2 = ops.attention_causal(q, k2, v2, scale)
+    assert np.array_equal(got2[:, :7], got[:, :7]) and not np.allclose(got2[:, 7:], got[:, 7:])
+    # without the mask the last query is the only one that agrees with plain attention
+    full = ops.attention(q, k, v, scale)
+    assert np.allclose(full[:, -1], got[:, -1], atol=1e-14) and not np.allclose(full[:, 0], got[:, 0])
+
+
 # ------------------------------------------------------------------- rope --
 
 def test_rope_rotation_properties():
