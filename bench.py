@@ -434,18 +434,36 @@ def atomization_study(args, B, inputs, torch):
     chain = MlpChain(layers, 8, "cuda")
     pool = [inputs.bits_to_torch(pool_bits[i], "cuda").contiguous() for i in range(64)]
     hp_requests = [chain.ops(x) for x in pool]
-    K, W = min(args.steps, 1500), min(args.warmup, 100)
+    K, W = max(1, min(args.steps, 1000)), max(0, min(args.warmup, 100))
     arrivals = inputs.poisson_arrivals(200.0, W + K, seed=3)
     rows = []
-    for m, n, k in ((4096, 4096, 4096), (8192, 8192, 8192), (16384, 16384, 8192), (16384, 16384, 16384)):
-        bf = torch.bfloat16
+    bf = torch.bfloat16
+
+    def gemm_kernel(m, n, k):
         a = (torch.randn((m, k), device="cuda", generator=torch.Generator("cuda").manual_seed(4)) * 0.5).to(bf)
         b = (torch.randn((k, n), device="cuda", generator=torch.Generator("cuda").manual_seed(5)) * 0.5).to(bf)
         c = torch.empty((m, n), dtype=bf, device="cuda")
-        op = B.gemm_op(a, b, c, m, n, k, tile=256)
-        wl = dict(hp_requests=hp_requests, be=dict(ops=[op], flop=2.0 * m * n * k))
+        return B.gemm_op(a, b, c, m, n, k, tile=256), 2.0 * m * n * k, "gemm %dx%dx%d" % (m, n, k)
+
+    def prefill_kernel(tokens):
+        # long-prompt attention prefill of a 32 / 8-head decoder layer (head width 128), one sequence
+        n_q, n_kv, d = 32, 8, 128
+        gen = torch.Generator("cuda").manual_seed(6)
+        q = torch.randn((tokens, n_q * d), device="cuda", generator=gen).to(bf)
+        kc = torch.randn((1, tokens, n_kv, d), device="cuda", generator=gen).to(bf)
+        vc = torch.randn((1, tokens, n_kv, d), device="cuda", generator=gen).to(bf)
+        o = torch.empty((tokens, n_q * d), dtype=bf, device="cuda")
+        op = B.attn_prefill_op(q, kc, vc, o, 1, n_q, n_kv, d, tokens, tokens, 1.0 / math.sqrt(d))
+        return op, 2.0 * tokens * tokens * d * n_q, "attention prefill %d tokens, 32/8 heads" % tokens      # causal: half of 4 T^2 d
+
+    kernels = [lambda: gemm_kernel(2048, 2048, 2048), lambda: gemm_kernel(4096, 4096, 4096), lambda: gemm_kernel(8192, 8192, 8192),
+               lambda: gemm_kernel(16384, 16384, 8192), lambda: gemm_kernel(16384, 16384, 16384),
+               lambda: prefill_kernel(2048), lambda: prefill_kernel(4096), lambda: prefill_kernel(8192), lambda: prefill_kernel(16384)]
+    for make in kernels:
+        op, flop, label = make()
+        wl = dict(hp_requests=hp_requests, be=dict(ops=[op], flop=flop))
         torch.cuda.synchronize()
-        row = {"be_gemm": "%dx%dx%d" % (m, n, k)}
+        row = {"be_kernel": label}
         for atomize in (0, 1):
             cfg = B.Config.default(atom_duration_us=args.atom_us, max_outstanding=args.max_outstanding,
                                    max_outstanding_hp=64, steal=1, atomize=atomize)
@@ -455,22 +473,25 @@ def atomization_study(args, B, inputs, torch):
                 row["be_kernel_us_256cu"] = B.lithos_time_launch(ctx, op, 0, p_all, 2, 5)[1]
                 parts = parts + [p_all]
             r = stacked_leg(B, torch, wl, t_hp, t_be, arrivals, W)
+            s_be = r["s1"]
             drop_world(B, ctx, parts, [t_hp, t_be])
             lat = r["lat"]
             row["atoms_on" if atomize else "atoms_off"] = {
                 "hp_p50_us": nearest_rank(lat, 0.5), "hp_p95_us": nearest_rank(lat, 0.95), "hp_p99_us": nearest_rank(lat, 0.99),
-                "be_tflops": r["be_iters"] * wl["be"]["flop"] / r["be_secs"] * 1e-12}
+                "be_tflops": r["be_iters"] * wl["be"]["flop"] / r["be_secs"] * 1e-12,
+                "be_atoms_per_kernel": (s_be.atoms / s_be.kernels) if s_be.kernels else None,
+                "be_revocations": int(s_be.revocations)}
         row["hp_p95_off_over_on"] = row["atoms_off"]["hp_p95_us"] / row["atoms_on"]["hp_p95_us"]
         row["hp_p99_off_over_on"] = row["atoms_off"]["hp_p99_us"] / row["atoms_on"]["hp_p99_us"]
         row["be_tflops_on_over_off"] = row["atoms_on"]["be_tflops"] / row["atoms_off"]["be_tflops"]
         rows.append(row)
-        del a, b, c, op, wl
+        del op, wl
         torch.cuda.empty_cache()
     line = {"metric": "atomization case study: high-priority tail with best-effort kernels of growing duration, atoms off / on",
-            "value": rows[-1]["hp_p99_off_over_on"], "unit": "x lower HP p99 with atomization (longest BE kernel)",
+            "value": max(r_["hp_p99_off_over_on"] for r_ in rows), "unit": "x lower HP p99 with atomization (longest BE kernel)",
             "n_gpus": 1, "steps": K, "warmup": W, "higher_is_better": True, "data": "synthetic", "dtype": "bf16",
             "config": {"workload": "atoms: cfg2 high-priority MLP (Poisson 200 req/s, 64-CU quota) + best-effort bf16 GEMMs "
-                                   "of growing size on 192 CUs, stealing on", "atom_duration_us": args.atom_us,
+                                   "of growing size, then attention prefills of growing prompt length, on 192 CUs, stealing on", "atom_duration_us": args.atom_us,
                        "max_outstanding": args.max_outstanding},
             "rows": rows,
             "paper_context": "LithOS on A100: atomization lowers HP P95 2x (BE training batch sweep) and 1.3x (BE sequence sweep); "
@@ -574,6 +595,7 @@ def rightsize_sweep(args, B, inputs, torch):
         kernels[k] = (o, 24)
     rows, full_cs, chosen_cs = [], 0.0, 0.0
     t_full, t_chosen, cu_time = 0.0, 0.0, 0.0
+    slip11_cu_time, slip11_time = 0.0, 0.0
     for name, (o, count) in kernels.items():
         r = B.lithos_rightsize(ctx, o, 8, 256, 8, 5, 50, 0.04)
         cus = list(r.cus[: r.n_points])
@@ -583,9 +605,16 @@ def rightsize_sweep(args, B, inputs, torch):
         mean = sum(lat) / len(lat)
         ss_tot = sum((v - mean) ** 2 for v in lat)
         r2 = 1.0 - sum((a - b) ** 2 for a, b in zip(lat, pred)) / ss_tot if ss_tot > 0 else 1.0
+        # the same sweep read at the paper's slip (k = 1.1, Section 7.2)
+        k11 = min(c for c, v in zip(cus, lat) if v <= 1.1 * r.full_us)
+        k11_us = lat[cus.index(k11)]
+        slip11_cu_time += count * k11 * k11_us
+        slip11_time += count * k11_us
         rows.append({"kernel": name, "launches_per_pass": count, "full_us": r.full_us, "chosen_cus": r.chosen_cus,
                      "chosen_us": r.chosen_us, "occupancy_bound_cus": r.occupancy_bound_cus,
-                     "model_cus": r.model_cus, "model_r2": r2, "curve_us": [round(v, 2) for v in lat]})
+                     "model_cus": r.model_cus, "online_cus": r.online_cus, "model_minus_sweep_cus": r.model_cus - r.chosen_cus,
+                     "online_minus_sweep_cus": r.online_cus - r.chosen_cus, "chosen_cus_slip_1.1": k11,
+                     "model_r2": r2, "curve_us": [round(v, 2) for v in lat]})
         t_full += count * r.full_us
         t_chosen += count * r.chosen_us
         cu_time += count * r.chosen_us * r.chosen_cus
@@ -661,6 +690,12 @@ def rightsize_sweep(args, B, inputs, torch):
            "measured_end_to_end_note": "kernels on different CU-masked queues are chained by events through the caller's stream "
                                        "(a queue's CU mask is fixed at creation); full_gpu_ms uses the same chaining on one queue",
            "measured_per_chain_mask": per_chain,
+           "fraction_of_cus_saved_at_slip_1.1": 1.0 - (slip11_cu_time / slip11_time) / 256.0,
+           "slowdown_at_slip_1.1": slip11_time / t_full - 1.0,
+           "model_vs_sweep": {"mean_abs_model_minus_sweep_cus": float(np.mean([abs(k["model_minus_sweep_cus"]) for k in rows])),
+                              "mean_abs_online_minus_sweep_cus": float(np.mean([abs(k["online_minus_sweep_cus"]) for k in rows])),
+                              "kernels_where_online_rule_within_16_cus": int(sum(abs(k["online_minus_sweep_cus"]) <= 16 for k in rows)),
+                              "kernels": len(rows)},
            "time_weighted_model_r2": sum(k["model_r2"] * k["launches_per_pass"] * k["full_us"] for k in rows) / t_full,
            "kernels": rows,
            "paper_context": "LithOS on A100: capacity savings up to 51 %, mean 26 %, at latency slip 1.1; R^2 0.92-0.99"}

@@ -52,7 +52,8 @@ enum {
     LITHOS_OP_SILU_MUL  = 9,  /* silu(gate) * up on a packed [rows, 2F] tensor */
     LITHOS_OP_SPIN      = 10, /* test kernel: every block spins a fixed number of clock ticks */
     LITHOS_OP_ATTN_MERGE = 11, /* second step of a split ATTN_DEC: merges the key ranges' partial softmaxes */
-    LITHOS_OP_SUM_SLICES = 12  /* second step of a K-sliced GEMM: adds the fp32 partial planes in slice order */
+    LITHOS_OP_SUM_SLICES = 12, /* second step of a K-sliced GEMM: adds the fp32 partial planes in slice order */
+    LITHOS_OP_ATTN_PREFILL = 13 /* causal self-attention over a whole prompt (query i sees keys 0..i), grouped-query */
 };
 
 #define LITHOS_ATTN_MAX_SPLITS 64
@@ -101,6 +102,10 @@ enum {
  *             partial softmaxes to the fp32 workspace in[3] (batch*n_q*splits*(d+2) floats) and
  *             leave o untouched; ATTN_MERGE on the same queue then produces o.
  * ATTN_MERGE  batch,n_q,n_kv,d,splits            workspace / o                        OUT_F32 as for ATTN_DEC
+ * ATTN_PREFILL batch,n_q,n_kv,d,T,cap             q,kcache,vcache / o                  ld0=q row stride, ld1=o row stride;
+ *             q [batch*T, ld0] and o [batch*T, ld1] bf16 with head h at columns h*d; the caches   fparam0=scale
+ *             [batch,cap,n_kv,d] bf16 hold the prompt's T keys and values; d = 128, T a multiple of 128.
+ *             One workgroup per (sequence, query head, 128 queries), the longest tiles first.
  * RMSNORM     rows,H                             x,w(f32) / y                         fparam0=eps
  * ROPE_KV     rows,n_q,n_kv,d,pos,cap            qkv[rows,(n_q+2n_kv)d] (in place) / kcache,vcache   fparam0=theta
  *             qkv is bf16, or fp32 with IN_F32; the caches are always bf16 (rounded on append)

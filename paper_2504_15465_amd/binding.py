@@ -20,7 +20,7 @@ OK, EINVAL, EHIP, EMASK, ESTATE, ELIMIT = 0, -1, -2, -3, -4, -5
 MASK_WORDS = 8
 MAX_SWEEP = 64
 
-OP_GEMM, OP_BIAS_ACT, OP_LAYERNORM, OP_SOFTMAX, OP_ATTN_ENC, OP_ATTN_DEC, OP_RMSNORM, OP_ROPE_KV, OP_SILU_MUL, OP_SPIN, OP_ATTN_MERGE, OP_SUM_SLICES = range(1, 13)
+OP_GEMM, OP_BIAS_ACT, OP_LAYERNORM, OP_SOFTMAX, OP_ATTN_ENC, OP_ATTN_DEC, OP_RMSNORM, OP_ROPE_KV, OP_SILU_MUL, OP_SPIN, OP_ATTN_MERGE, OP_SUM_SLICES, OP_ATTN_PREFILL = range(1, 14)
 ATTN_MAX_SPLITS = 64
 F_TRANS_A, F_TRANS_B, F_BIAS, F_GELU, F_RESIDUAL, F_OUT_F32, F_IN_F32, F_SPLIT_A, F_OUT_SPLIT = (1 << i for i in range(9))
 TILE_AUTO, TILE_SKINNY, TILE_64, TILE_128, TILE_256 = 0, 1, 64, 128, 256
@@ -234,6 +234,13 @@ def attn_dec_op(q, kcache, vcache, o, batch, n_q, n_kv, d, keys, cap, scale, ldq
     ins = (q, kcache, vcache) if workspace is None else (q, kcache, vcache, workspace)
     return make_op(OP_ATTN_DEC, (batch, n_q, n_kv, d, keys, cap, splits), flags, ld=(ldq if ldq is not None else n_q * d,),
                    fparam=(scale,), inputs=ins, outputs=(o,), op_id=op_id)
+
+
+def attn_prefill_op(q, kcache, vcache, o, batch, n_q, n_kv, d, tokens, cap, scale, ldq=None, ldo=None, op_id=0) -> Op:
+    """Causal self-attention over a prompt of ``tokens`` positions per sequence (query i sees keys 0..i)."""
+    return make_op(OP_ATTN_PREFILL, (batch, n_q, n_kv, d, tokens, cap), 0,
+                   ld=(ldq if ldq is not None else n_q * d, ldo if ldo is not None else n_q * d),
+                   fparam=(scale,), inputs=(q, kcache, vcache), outputs=(o,), op_id=op_id)
 
 
 def attn_workspace_floats(batch, n_q, d, splits) -> int:

@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "liblithos.so")
 
-SOURCES = ["gemm_tile256_wide.hip", "gemm_tile256_elem.hip", "gemm_lds256_wide.hip", "gemm_lds256_elem.hip", "gemm_tile128.hip", "gemm_tile64.hip", "gemm_skinny.hip", "gemm.hip", "rowops.hip", "attention.hip", "runtime.hip", "sched.hip", "sched_core.cpp"]
+SOURCES = ["gemm_tile256_wide.hip", "gemm_tile256_elem.hip", "gemm_lds256_wide.hip", "gemm_lds256_elem.hip", "gemm_tile128.hip", "gemm_tile64.hip", "gemm_skinny.hip", "gemm.hip", "rowops.hip", "attention.hip", "attention_prefill.hip", "runtime.hip", "sched.hip", "sched_core.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -43,6 +43,8 @@ int rowops_plan(const lithos_op_t& op, OpPlan* plan);
 int rowops_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, hipStream_t s);
 int attn_plan(const lithos_op_t& op, OpPlan* plan);
 int attn_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, hipStream_t s);
+int attn_prefill_plan(const lithos_op_t& op, OpPlan* plan);
+int attn_prefill_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, hipStream_t s);
 int spin_plan(const lithos_op_t& op, OpPlan* plan);
 int spin_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, hipStream_t s);
 int probe_launch(uint32_t n_wg, uint32_t* dev_xcd, uint32_t* dev_hwid, hipStream_t s);

@@ -100,6 +100,7 @@ int op_plan(const lithos_op_t& op, OpPlan* plan)
     case LITHOS_OP_ATTN_ENC:
     case LITHOS_OP_ATTN_MERGE:
     case LITHOS_OP_ATTN_DEC: return attn_plan(op, plan);
+    case LITHOS_OP_ATTN_PREFILL: return attn_prefill_plan(op, plan);
     case LITHOS_OP_BIAS_ACT:
     case LITHOS_OP_LAYERNORM:
     case LITHOS_OP_SOFTMAX:
@@ -120,6 +121,7 @@ int op_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom, h
     case LITHOS_OP_ATTN_ENC:
     case LITHOS_OP_ATTN_MERGE:
     case LITHOS_OP_ATTN_DEC: return attn_launch(op, plan, atom, s);
+    case LITHOS_OP_ATTN_PREFILL: return attn_prefill_launch(op, plan, atom, s);
     default: return rowops_launch(op, plan, atom, s);
     }
 }

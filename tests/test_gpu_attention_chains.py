@@ -164,3 +164,73 @@ def test_decoder_chain_matches_oracle(batch, n_layers, pos):
     assert err.max() <= 2e-3
     run_ops(ctx(), chain.ops(), None, atom_blocks=5)
     assert bits_equal(chain.out, out)
+
+
+@pytest.mark.parametrize("batch,n_q,n_kv,tokens", [(1, 4, 4, 128), (2, 8, 2, 384), (1, 4, 1, 1024), (1, 2, 2, 640)])
+def test_prefill_attention(batch, n_q, n_kv, tokens):
+    """Causal attention over a whole prompt, element by element against the oracle; several query tiles,
+    the diagonal blocks where the mask cuts through a key block, grouped-query sharing, a cache longer
+    than the prompt; atomized == whole and every (sequence, head, query tile) exactly once."""
+    d, cap = 128, tokens + 64
+    qb = inputs.normal_bits((batch * tokens, n_q * d), 51)
+    kb = inputs.normal_bits((batch, cap, n_kv, d), 52)
+    vb = inputs.normal_bits((batch, cap, n_kv, d), 53)
+    scale = 1 / math.sqrt(d)
+    ref = O.attention_causal(O.bf16_to_f64(qb).reshape(batch, tokens, n_q, d), O.bf16_to_f64(kb)[:, :tokens],
+                             O.bf16_to_f64(vb)[:, :tokens], scale).reshape(batch * tokens, n_q * d)
+    q, k, v = dev_bits(qb), dev_bits(kb), dev_bits(vb)
+    o = nan_like((batch * tokens, n_q * d), torch.bfloat16)
+    total = launch(B.attn_prefill_op(q, k, v, o, batch, n_q, n_kv, d, tokens, cap, scale))
+    assert total == batch * n_q * (tokens // 128)
+    g = o.cpu().to(torch.float64).numpy()
+    assert not np.isnan(g).any()
+    # probabilities are rounded to bf16 (2^-9 relative each, averaged over the visible keys) and the
+    # output to bf16 (2^-9 of |o| <= ~4 for the first queries, which see few keys)
+    err = np.abs(g - ref)
+    assert (err <= 2.0 ** -8 * np.abs(ref) + 4e-3).all(), err.max()
+    assert err.mean() <= 1e-3
+    oa = nan_like(o.shape, torch.bfloat16)
+    launch(B.attn_prefill_op(q, k, v, oa, batch, n_q, n_kv, d, tokens, cap, scale), atom_blocks=3)
+    assert bits_equal(o, oa)
+
+
+def test_prefill_attention_at_full_size_on_sampled_queries():
+    """8192-token prompt, 32 query / 8 key-value heads (the best-effort kernel of the atomization study):
+    sampled (query, head) outputs against the oracle's attention of that query over its key prefix."""
+    batch, n_q, n_kv, d, tokens = 1, 32, 8, 128, 8192
+    qb = inputs.normal_bits((tokens, n_q * d), 54)
+    kb = inputs.normal_bits((1, tokens, n_kv, d), 55)
+    vb = inputs.normal_bits((1, tokens, n_kv, d), 56)
+    scale = 1 / math.sqrt(d)
+    q, k, v = dev_bits(qb), dev_bits(kb), dev_bits(vb)
+    o = nan_like((tokens, n_q * d), torch.bfloat16)
+    part = B.lithos_create_partition(ctx(), B.lithos_make_mask(ctx(), 192, B.MASK_STRIPED, 64))
+    try:
+        torch.cuda.synchronize()
+        B.lithos_launch_atomized(ctx(), B.attn_prefill_op(q, k, v, o, batch, n_q, n_kv, d, tokens, tokens, scale), (0, 0, 0), 384, part, None)
+        B.lithos_partition_sync(ctx(), part)
+    finally:
+        B.lithos_destroy_partition(part)
+    g = o.cpu().to(torch.float64).numpy()
+    assert not np.isnan(g).any()
+    rng = np.random.default_rng(5)
+    k64, v64 = O.bf16_to_f64(kb), O.bf16_to_f64(vb)
+    for qi in [0, 1, 63, 64, 127, 128, 4095, 4096, 8191] + [int(x) for x in rng.integers(0, tokens, 12)]:
+        qrow = O.bf16_to_f64(qb[qi:qi + 1]).reshape(1, 1, n_q, d)
+        ref = O.attention(qrow, k64[:, :qi + 1], v64[:, :qi + 1], scale).reshape(n_q * d)
+        err = np.abs(g[qi] - ref)
+        assert (err <= 2.0 ** -8 * np.abs(ref) + 4e-3).all(), (qi, err.max())
+
+
+def test_prefill_attention_refuses_unbuilt_shapes():
+    x = torch.zeros((256, 4 * 128), dtype=torch.bfloat16, device="cuda")
+    kv = torch.zeros((1, 256, 4, 128), dtype=torch.bfloat16, device="cuda")
+    bad = [B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 64, 256, 256, 1.0),        # head width 64
+           B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 128, 200, 256, 1.0),       # not a multiple of 128
+           B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 128, 512, 256, 1.0),       # longer than the buffers
+           B.attn_prefill_op(x, kv, kv, x, 1, 4, 3, 128, 256, 256, 1.0),       # 3 does not divide 4
+           B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 128, 256, 256, 1.0, ldq=256)]
+    for op in bad:
+        with pytest.raises(B.LithosError) as e:
+            B.lithos_launch_atomized(ctx(), op)
+        assert e.value.code == B.EINVAL
