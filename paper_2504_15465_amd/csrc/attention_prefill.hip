@@ -15,8 +15,8 @@
 // product; the normalisation is applied to the fp32 result.
 //
 // The tile a workgroup computes is named by its LOGICAL block index (LithOS Section 4.4), so
-// any sub-range of blocks is a valid atom.  Tiles are numbered from the end of the prompt: the
-// longest ones (most keys) come first in a launch.
+// any sub-range of blocks is a valid atom.  Tiles are numbered from the end of the prompt (the
+// longest ones, with most keys, come first in a launch), all heads of one tile side by side.
 #include "common.hpp"
 #include <math.h>
 
@@ -76,9 +76,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs a, Ato
     __shared__ __attribute__((aligned(16))) uint16_t Vs[PF_KB * PF_D];
 
     const uint32_t L = atom_logical_block(atom);
+    // x = query head (fastest), y = sequence, z = tile rank: neighbouring logical blocks are the same
+    // query tile of all heads, so the blocks of one atom run about equally long and the heads that
+    // share a key/value head stream the same keys side by side
     const int nqt = a.T / PF_QT;
-    const int qtile = nqt - 1 - (int)(L % nqt);            // longest tiles first
-    const int h = (int)((L / nqt) % a.n_q), b = (int)(L / ((uint32_t)nqt * a.n_q));
+    const int h = (int)(L % a.n_q), b = (int)((L / a.n_q) % a.batch);
+    const int qtile = nqt - 1 - (int)(L / ((uint32_t)a.n_q * a.batch));     // longest tiles first
     const int g = h / (a.n_q / a.n_kv);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
@@ -223,7 +226,7 @@ int attn_prefill_plan(const lithos_op_t& op, OpPlan* plan)
     if (op.flags & (LITHOS_F_IN_F32 | LITHOS_F_OUT_F32 | LITHOS_F_OUT_SPLIT)) return fail(LITHOS_EINVAL, "attn_prefill: bf16 in, bf16 out only");
     const int64_t total = batch * n_q * (T / PF_QT);
     if (total > 0x7fffffff) return fail(LITHOS_EINVAL, "attn_prefill: too many workgroups");
-    plan->grid = {(uint32_t)(T / PF_QT), (uint32_t)n_q, (uint32_t)batch};
+    plan->grid = {(uint32_t)n_q, (uint32_t)batch, (uint32_t)(T / PF_QT)};
     plan->total = (uint32_t)total;
     plan->threads = 256;
     plan->variant = 0;

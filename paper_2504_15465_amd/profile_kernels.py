@@ -20,12 +20,15 @@ from .models import DecoderChain, EncoderChain, MlpChain, training_block_ops
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "mlp", "skinny", "encoder", "decoder", "train", "atom_sweep"])
+    ap.add_argument("--what", default="gemm8192", choices=["gemm8192", "gemm8192_atoms", "prefill", "mlp", "skinny", "encoder", "decoder", "train", "atom_sweep"])
     ap.add_argument("--tile", type=int, default=256)
     ap.add_argument("--batch", type=int, default=4)
     ap.add_argument("--layers", type=int, default=4)
     ap.add_argument("--reps", type=int, default=5)
+    ap.add_argument("--warm", type=int, default=0, help="gemm8192: launches before the --reps ones (the profiler sees them too; "
+                    "profile_summary --skip sets them apart), so that the clocks have settled")
     ap.add_argument("--cus", type=int, default=256)
+    ap.add_argument("--tokens", type=int, default=8192, help="prefill: prompt length")
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--nt", action="store_true", help="gemm8192: B stored [N,K] (TRANS_B)")
     args = ap.parse_args()
@@ -48,9 +51,21 @@ def main():
         grid, wg = B.lithos_op_grid(ctx, op)
         atom = 0 if args.what == "gemm8192" else args.cus * wg
         torch.cuda.synchronize()
-        for _ in range(args.reps):
+        for _ in range(args.warm + args.reps):
             B.lithos_launch_atomized(ctx, op, (0, 0, 0), atom, part, None)
         B.lithos_partition_sync(ctx, part)
+    elif args.what == "prefill":        # causal attention over one prompt of --tokens positions, 32 / 8 heads of 128
+        import math
+        n_q, n_kv, d, T = 32, 8, 128, args.tokens
+        q = inputs.bits_to_torch(inputs.normal_bits((T, n_q * d), 54), "cuda")
+        kc = inputs.bits_to_torch(inputs.normal_bits((1, T, n_kv, d), 55), "cuda")
+        vc = inputs.bits_to_torch(inputs.normal_bits((1, T, n_kv, d), 56), "cuda")
+        o = torch.empty((T, n_q * d), dtype=torch.bfloat16, device="cuda")
+        op = B.attn_prefill_op(q, kc, vc, o, 1, n_q, n_kv, d, T, T, 1.0 / math.sqrt(d))
+        torch.cuda.synchronize()
+        mean, med = B.lithos_time_launch(ctx, op, 0, part, args.warm + 2, args.reps)
+        flop = 2.0 * T * T * d * n_q
+        print("prefill %d tokens on %d CUs: median %.1f us, %.0f TFLOP/s (causal flops)" % (T, args.cus, med, flop / med * 1e-6))
     elif args.what in ("mlp", "skinny"):
         layers = inputs.mlp_params(6, 4096, seed=1)
         chain = MlpChain(layers, 8)
