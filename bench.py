@@ -23,6 +23,8 @@ Other workloads (same JSON layout, not the headline):
   --workload cfg4   right-sizing sweep over every kernel of cfg3 (CU counts 8..256 step 8)
   --workload three  two high-priority tenants (quotas 128 and 64 CUs) and a best-effort tenant (64 CUs)
                     that lives on the CUs the other two leave idle (paper Section 7.1, inference-only stacking)
+  --workload roofline  only the roofline leg of the default run (the 8192^3 GEMM whole, 256 CUs): the
+                    command whose rocprofv3 kernel trace is kept under profiles/
   --workload atoms  atomization case study (paper Section 7.4): the cfg2 high-priority tenant against
                     best-effort GEMMs of growing duration, kernel atomization off and on
 """
@@ -219,12 +221,54 @@ def stacked_leg(B, torch, wl, t_hp, t_be, arrivals, warm):
     return dict(lat=lat, wall=wall, be_iters=iters, be_secs=secs, s0=s0, s1=s1)
 
 
+def time_whole_and_atomized(B, np, ctx, op, flop, atom_blocks, part, rounds=8, reps=5):
+    """The dominant kernel whole and cut in atoms of `atom_blocks`, on the queue of `part`, bracketed by
+    HIP events on that queue (lithos_time_launch).  Whole and atomized launches alternate in short rounds
+    so that clock and thermal drift hits both alike; medians for the overhead, the mean of the whole
+    launches for the roofline."""
+    B.lithos_time_launch(ctx, op, 0, part, 3, 3)
+    rs = [(B.lithos_time_launch(ctx, op, 0, part, 1, reps), B.lithos_time_launch(ctx, op, atom_blocks, part, 1, reps))
+          for _ in range(rounds)]
+    whole_mean = float(np.mean([w[0] for w, _ in rs]))
+    whole_med = float(np.median([w[1] for w, _ in rs]))
+    at_med = float(np.median([a[1] for _, a in rs]))
+    return {"whole_mean_us": whole_mean, "whole_median_us": whole_med, "atomized_median_us": at_med,
+            "launches_timed": reps * rounds, "overhead_pct": (at_med - whole_med) / whole_med * 100.0,
+            "achieved_tflops": flop / (whole_mean * 1e-6) * 1e-12}
+
+
+def roofline_only(args, B, inputs, torch):
+    """Only the roofline leg of the default run: the best-effort 8192^3 GEMM, whole launches on a 256-CU
+    queue after the GPU has been kept busy for a while (so that a profiler trace of this command shows the
+    same kernel durations as the line it prints)."""
+    import numpy as np
+    be = be_gemm_8192(B, inputs, torch, args.be_tile)
+    op, flop, desc = be["dominant"]
+    ctx = B.lithos_init(0, None)
+    part = B.lithos_create_partition(ctx, B.lithos_make_mask(ctx, 256, B.MASK_STRIPED, 0))
+    grid, wg_per_cu = B.lithos_op_grid(ctx, op)
+    torch.cuda.synchronize()
+    B.lithos_time_launch(ctx, op, 0, part, 0, args.warmup if args.warmup > 0 else 200)      # settle the clocks
+    roof = time_whole_and_atomized(B, np, ctx, op, flop, 256 * wg_per_cu, part, rounds=max(1, args.steps // 5))
+    B.lithos_destroy_partition(part)
+    B.lithos_shutdown(ctx)
+    traffic = TRAFFIC_BYTES.get(args.be_tile)
+    print(json.dumps({"metric": "roofline of the dominant kernel", "value": roof["achieved_tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+                      "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": desc, "untimed_launches_before": args.warmup if args.warmup > 0 else 200},
+                      "atom_overhead_pct": roof["overhead_pct"],
+                      "roofline": {"bound": "mfma", "kernel": desc, "achieved": roof["achieved_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                                   "unit": "TFLOP/s", "frac": roof["achieved_tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
+                                   "traffic_over_algorithmic": (traffic / ALGORITHMIC_BYTES_8192) if traffic else None,
+                                   "launch_us": roof["whole_mean_us"], "launches_timed": roof["launches_timed"], "flop_per_launch": flop}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "atoms", "three"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "atoms", "three", "roofline"])
     ap.add_argument("--batch", type=int, default=8, help="cfg3/cfg5 high-priority batch size")
     ap.add_argument("--layers", type=int, default=32, help="cfg5 decoder layers")
     ap.add_argument("--atom-us", type=float, default=250.0)
@@ -256,6 +300,8 @@ def main():
         return three_tenants(args, B, inputs, torch)
     if args.workload == "atoms":
         return atomization_study(args, B, inputs, torch)
+    if args.workload == "roofline":
+        return roofline_only(args, B, inputs, torch)
     K, W = args.steps, args.warmup
     wl = {"cfg2": wl_cfg2, "cfg3": wl_cfg3, "cfg5": wl_cfg5}[args.workload](args, B, inputs, torch)
     torch.cuda.synchronize()
@@ -342,17 +388,9 @@ def main():
     atoms_per_kernel = max(1.0, (s1.atoms - s0.atoms) / max(1, (s1.kernels - s0.kernels)))
     quantum = 256 * wg_per_cu
     atom_blocks = min(total_blocks, -(-int(math.ceil(total_blocks / atoms_per_kernel)) // quantum) * quantum)
-    # whole and atomized launches alternate in short rounds so that clock and thermal
-    # drift hits both alike; the figures are medians (means for the roofline) over the rounds
-    B.lithos_time_launch(ctx, op, 0, p_all, 3, 3)
-    rounds = [(B.lithos_time_launch(ctx, op, 0, p_all, 1, 5), B.lithos_time_launch(ctx, op, atom_blocks, p_all, 1, 5))
-              for _ in range(8)]
-    whole_mean = float(np.mean([w[0] for w, _ in rounds]))
-    n_roof = 5 * len(rounds)
-    whole_med = float(np.median([w[1] for w, _ in rounds]))
-    at_med = float(np.median([a[1] for _, a in rounds]))
-    overhead_pct = (at_med - whole_med) / whole_med * 100.0
-    achieved = flop / (whole_mean * 1e-6) * 1e-12
+    roof = time_whole_and_atomized(B, np, ctx, op, flop, atom_blocks, p_all)
+    whole_mean, n_roof, whole_med, at_med = roof["whole_mean_us"], roof["launches_timed"], roof["whole_median_us"], roof["atomized_median_us"]
+    overhead_pct, achieved = roof["overhead_pct"], roof["achieved_tflops"]
     drop_world(B, ctx, parts + [p_all], [t_hp, t_be])
     # the same atoms in the paper's Prelude form (every atom launches the whole grid, blocks outside
     # the range exit at once): the early-exit traffic the remapping form avoids

@@ -105,8 +105,9 @@ enum {
  * ATTN_PREFILL batch,n_q,n_kv,d,T,cap             q,kcache,vcache / o                  ld0=q row stride, ld1=o row stride;
  *             q [batch*T, ld0] and o [batch*T, ld1] bf16 with head h at columns h*d; the caches   fparam0=scale
  *             [batch,cap,n_kv,d] bf16 hold the prompt's T keys and values; d = 128, T a multiple of 128.
- *             One workgroup per (128 queries, sequence, query head): grid x = head, y = sequence, z = tile,
- *             tiles numbered from the end of the prompt (the longest first).
+ *             One workgroup per (128 queries, sequence, query head), tiles numbered from the end of the
+ *             prompt (the longest first) in groups of up to 16; grid x = heads of a key/value head x tiles of
+ *             a group, y = key/value head x sequence, z = tile group.
  * RMSNORM     rows,H                             x,w(f32) / y                         fparam0=eps
  * ROPE_KV     rows,n_q,n_kv,d,pos,cap            qkv[rows,(n_q+2n_kv)d] (in place) / kcache,vcache   fparam0=theta
  *             qkv is bf16, or fp32 with IN_F32; the caches are always bf16 (rounded on append)

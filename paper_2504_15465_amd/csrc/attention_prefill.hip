@@ -16,7 +16,8 @@
 //
 // The tile a workgroup computes is named by its LOGICAL block index (LithOS Section 4.4), so
 // any sub-range of blocks is a valid atom.  Tiles are numbered from the end of the prompt (the
-// longest ones, with most keys, come first in a launch), all heads of one tile side by side.
+// longest ones, with most keys, come first in a launch), in groups that keep the blocks sharing
+// keys and values next to each other (see the kernel).
 #include "common.hpp"
 #include <math.h>
 
@@ -47,6 +48,14 @@ __device__ __forceinline__ int pf_k_index(int key, int chunk) { return key * PF_
 // transposing load touches fall into different banks.
 __device__ __forceinline__ int pf_v_index(int key, int d) { return key * PF_D + ((((d >> 3) ^ ((key & 3) << 2))) << 3) + (d & 7); }
 
+// query tiles per group in the block order: the largest power of two up to 16 that divides the tile count
+__host__ __device__ __forceinline__ int pf_tile_group(int nqt)
+{
+    int r = 16;
+    while (nqt % r) r >>= 1;
+    return r;
+}
+
 __device__ __forceinline__ uint32_t pf_pack_bf16(float lo, float hi)
 {
     pf_f32x2 f = {lo, hi};
@@ -76,13 +85,19 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs a, Ato
     __shared__ __attribute__((aligned(16))) uint16_t Vs[PF_KB * PF_D];
 
     const uint32_t L = atom_logical_block(atom);
-    // x = query head (fastest), y = sequence, z = tile rank: neighbouring logical blocks are the same
-    // query tile of all heads, so the blocks of one atom run about equally long and the heads that
-    // share a key/value head stream the same keys side by side
-    const int nqt = a.T / PF_QT;
-    const int h = (int)(L % a.n_q), b = (int)((L / a.n_q) % a.batch);
-    const int qtile = nqt - 1 - (int)(L / ((uint32_t)a.n_q * a.batch));     // longest tiles first
-    const int g = h / (a.n_q / a.n_kv);
+    // Order of the logical blocks, fastest first: the query heads of one key/value head, R
+    // neighbouring query tiles, key/value head, sequence, group of R tiles (longest first).
+    // 64 neighbouring blocks (what one die holds at a time when 4 heads share a key/value head
+    // and R = 16) then stream the SAME keys and values through that die's L2, and the blocks of
+    // an atom differ in length by at most R tiles of the prompt's T/128.
+    const int nqt = a.T / PF_QT, R = pf_tile_group(nqt), G = a.n_q / a.n_kv;
+    uint32_t rest = L;
+    const int hq = (int)(rest % G); rest /= G;
+    const int r = (int)(rest % R); rest /= R;
+    const int g = (int)(rest % a.n_kv); rest /= a.n_kv;
+    const int b = (int)(rest % a.batch); rest /= a.batch;
+    const int qtile = nqt - 1 - ((int)rest * R + r);
+    const int h = g * G + hq;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int q0 = qtile * PF_QT + wave * 32;               // this wavefront's first query
@@ -226,7 +241,8 @@ int attn_prefill_plan(const lithos_op_t& op, OpPlan* plan)
     if (op.flags & (LITHOS_F_IN_F32 | LITHOS_F_OUT_F32 | LITHOS_F_OUT_SPLIT)) return fail(LITHOS_EINVAL, "attn_prefill: bf16 in, bf16 out only");
     const int64_t total = batch * n_q * (T / PF_QT);
     if (total > 0x7fffffff) return fail(LITHOS_EINVAL, "attn_prefill: too many workgroups");
-    plan->grid = {(uint32_t)n_q, (uint32_t)batch, (uint32_t)(T / PF_QT)};
+    const int R = pf_tile_group((int)(T / PF_QT));
+    plan->grid = {(uint32_t)(n_q / n_kv * R), (uint32_t)(n_kv * batch), (uint32_t)(T / PF_QT / R)};
     plan->total = (uint32_t)total;
     plan->threads = 256;
     plan->variant = 0;
