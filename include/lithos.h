@@ -104,10 +104,10 @@ enum {
  * ATTN_MERGE  batch,n_q,n_kv,d,splits            workspace / o                        OUT_F32 as for ATTN_DEC
  * ATTN_PREFILL batch,n_q,n_kv,d,T,cap             q,kcache,vcache / o                  ld0=q row stride, ld1=o row stride;
  *             q [batch*T, ld0] and o [batch*T, ld1] bf16 with head h at columns h*d; the caches   fparam0=scale
- *             [batch,cap,n_kv,d] bf16 hold the prompt's T keys and values; d = 128, T a multiple of 128.
- *             One workgroup per (128 queries, sequence, query head), tiles numbered from the end of the
- *             prompt (the longest first) in groups of up to 16; grid x = heads of a key/value head x tiles of
- *             a group, y = key/value head x sequence, z = tile group.
+ *             [batch,cap,n_kv,d] bf16 hold the prompt's T keys and values; d = 128, T a multiple of 256.
+ *             One workgroup per (pair of 128-query tiles, sequence, query head): tile p from the end and
+ *             tile p from the start of the prompt, so that every block sees T/128 + 1 tiles of keys; grid
+ *             x = heads of a key/value head x pairs, y = key/value head, z = sequence.
  * RMSNORM     rows,H                             x,w(f32) / y                         fparam0=eps
  * ROPE_KV     rows,n_q,n_kv,d,pos,cap            qkv[rows,(n_q+2n_kv)d] (in place) / kcache,vcache   fparam0=theta
  *             qkv is bf16, or fp32 with IN_F32; the caches are always bf16 (rounded on append)

@@ -1,6 +1,8 @@
 // Atom-aware causal attention over a long prompt (prefill), grouped-query, head width 128.
 //
-// One workgroup per (sequence, query head, tile of 128 queries); each of its four wavefronts
+// One workgroup per (sequence, query head, PAIR of 128-query tiles: tile p from the end and tile p
+// from the start of the prompt, which together see the same number of keys for every p); for each
+// tile in turn, each of the four wavefronts
 // owns 32 queries and walks the keys 0 .. last query of the tile in blocks of 64 with a running
 // softmax (maximum, denominator and unnormalised output per query).  Both products run on MFMA
 // (v_mfma_f32_32x32x16_bf16):
@@ -15,9 +17,7 @@
 // product; the normalisation is applied to the fp32 result.
 //
 // The tile a workgroup computes is named by its LOGICAL block index (LithOS Section 4.4), so
-// any sub-range of blocks is a valid atom.  Tiles are numbered from the end of the prompt (the
-// longest ones, with most keys, come first in a launch), in groups that keep the blocks sharing
-// keys and values next to each other (see the kernel).
+// any sub-range of blocks is a valid atom, and every block does the same amount of work.
 #include "common.hpp"
 #include <math.h>
 
@@ -48,14 +48,6 @@ __device__ __forceinline__ int pf_k_index(int key, int chunk) { return key * PF_
 // transposing load touches fall into different banks.
 __device__ __forceinline__ int pf_v_index(int key, int d) { return key * PF_D + ((((d >> 3) ^ ((key & 3) << 2))) << 3) + (d & 7); }
 
-// query tiles per group in the block order: the largest power of two up to 16 that divides the tile count
-__host__ __device__ __forceinline__ int pf_tile_group(int nqt)
-{
-    int r = 16;
-    while (nqt % r) r >>= 1;
-    return r;
-}
-
 __device__ __forceinline__ uint32_t pf_pack_bf16(float lo, float hi)
 {
     pf_f32x2 f = {lo, hi};
@@ -85,21 +77,26 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs a, Ato
     __shared__ __attribute__((aligned(16))) uint16_t Vs[PF_KB * PF_D];
 
     const uint32_t L = atom_logical_block(atom);
-    // Order of the logical blocks, fastest first: the query heads of one key/value head, R
-    // neighbouring query tiles, key/value head, sequence, group of R tiles (longest first).
-    // 64 neighbouring blocks (what one die holds at a time when 4 heads share a key/value head
-    // and R = 16) then stream the SAME keys and values through that die's L2, and the blocks of
-    // an atom differ in length by at most R tiles of the prompt's T/128.
-    const int nqt = a.T / PF_QT, R = pf_tile_group(nqt), G = a.n_q / a.n_kv;
+    // A block computes TWO query tiles, number p from the end of the prompt and number p from its
+    // start: together they see T/128 + 1 tiles of keys whatever p is, so all blocks of the grid do the
+    // same work (a causal tile alone sees between 1 and T/128 tiles).  Order of the logical blocks,
+    // fastest first: the query heads of one key/value head, the pair p, key/value head, sequence:
+    // neighbouring blocks stream the same keys and values through one die's L2.
+    const int nqt = a.T / PF_QT, npair = nqt / 2, G = a.n_q / a.n_kv;
     uint32_t rest = L;
     const int hq = (int)(rest % G); rest /= G;
-    const int r = (int)(rest % R); rest /= R;
+    const int pr = (int)(rest % npair); rest /= npair;
     const int g = (int)(rest % a.n_kv); rest /= a.n_kv;
-    const int b = (int)(rest % a.batch); rest /= a.batch;
-    const int qtile = nqt - 1 - ((int)rest * R + r);
+    const int b = (int)rest;
     const int h = g * G + hq;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
+    const int64_t tok = (int64_t)a.n_kv * PF_D;
+    const uint16_t* kg = a.k + ((int64_t)b * a.cap * a.n_kv + g) * PF_D;
+    const uint16_t* vg = a.v + ((int64_t)b * a.cap * a.n_kv + g) * PF_D;
+
+  for (int pass = 0; pass < 2; ++pass) {
+    const int qtile = pass == 0 ? nqt - 1 - pr : pr;        // the long tile first
     const int q0 = qtile * PF_QT + wave * 32;               // this wavefront's first query
     const int qi = q0 + l32;                                // this lane's query
 
@@ -111,9 +108,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs a, Ato
         for (int ds = 0; ds < PF_D / 16; ++ds) qf[ds] = __builtin_bit_cast(pf_bf16x8, *reinterpret_cast<const uint4*>(qp + ds * 16));
     }
 
-    const int64_t tok = (int64_t)a.n_kv * PF_D;
-    const uint16_t* kg = a.k + ((int64_t)b * a.cap * a.n_kv + g) * PF_D;
-    const uint16_t* vg = a.v + ((int64_t)b * a.cap * a.n_kv + g) * PF_D;
     uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
     pf_f32x16 o[PF_D / 32];
 #pragma unroll
@@ -218,6 +212,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs a, Ato
             *reinterpret_cast<uint2*>(op + db * 32 + 8 * q4 + 4 * half) =
                 make_uint2(pf_pack_bf16(o[db][4 * q4] * inv, o[db][4 * q4 + 1] * inv),
                            pf_pack_bf16(o[db][4 * q4 + 2] * inv, o[db][4 * q4 + 3] * inv));
+  }
 }
 
 #undef PF_FETCH
@@ -231,7 +226,7 @@ int attn_prefill_plan(const lithos_op_t& op, OpPlan* plan)
     const int64_t batch = op.dim[0], n_q = op.dim[1], n_kv = op.dim[2], d = op.dim[3], T = op.dim[4], cap = op.dim[5];
     if (batch <= 0 || n_q <= 0 || n_kv <= 0 || n_q % n_kv) return fail(LITHOS_EINVAL, "attn_prefill: need batch > 0 and n_kv dividing n_q");
     if (d != PF_D) return fail(LITHOS_EINVAL, "attn_prefill: head width %lld is not built (128 only)", (long long)d);
-    if (T <= 0 || T % PF_QT) return fail(LITHOS_EINVAL, "attn_prefill: prompt length %lld must be a positive multiple of %d", (long long)T, PF_QT);
+    if (T <= 0 || T % (2 * PF_QT)) return fail(LITHOS_EINVAL, "attn_prefill: prompt length %lld must be a positive multiple of %d", (long long)T, 2 * PF_QT);
     if (T > cap) return fail(LITHOS_EINVAL, "attn_prefill: prompt longer than the key/value buffers (cap)");
     if (op.ld[0] < n_q * d || op.ld[1] < n_q * d || op.ld[0] % 8 || op.ld[1] % 4)
         return fail(LITHOS_EINVAL, "attn_prefill: row strides of q (multiple of 8) and o (multiple of 4) must be at least n_q*d");
@@ -239,10 +234,9 @@ int attn_prefill_plan(const lithos_op_t& op, OpPlan* plan)
     if (!aligned16(op.in[0]) || !aligned16(op.in[1]) || !aligned16(op.in[2]) || (reinterpret_cast<uintptr_t>(op.out[0]) & 7u))
         return fail(LITHOS_EINVAL, "attn_prefill: q, k, v must be 16-byte aligned, o 8-byte aligned");
     if (op.flags & (LITHOS_F_IN_F32 | LITHOS_F_OUT_F32 | LITHOS_F_OUT_SPLIT)) return fail(LITHOS_EINVAL, "attn_prefill: bf16 in, bf16 out only");
-    const int64_t total = batch * n_q * (T / PF_QT);
+    const int64_t total = batch * n_q * (T / PF_QT / 2);
     if (total > 0x7fffffff) return fail(LITHOS_EINVAL, "attn_prefill: too many workgroups");
-    const int R = pf_tile_group((int)(T / PF_QT));
-    plan->grid = {(uint32_t)(n_q / n_kv * R), (uint32_t)(n_kv * batch), (uint32_t)(T / PF_QT / R)};
+    plan->grid = {(uint32_t)(n_q / n_kv * (T / PF_QT / 2)), (uint32_t)n_kv, (uint32_t)batch};
     plan->total = (uint32_t)total;
     plan->threads = 256;
     plan->variant = 0;

@@ -166,11 +166,11 @@ def test_decoder_chain_matches_oracle(batch, n_layers, pos):
     assert bits_equal(chain.out, out)
 
 
-@pytest.mark.parametrize("batch,n_q,n_kv,tokens", [(1, 4, 4, 128), (2, 8, 2, 384), (1, 4, 1, 1024), (1, 2, 2, 640)])
+@pytest.mark.parametrize("batch,n_q,n_kv,tokens", [(1, 4, 4, 256), (2, 8, 2, 512), (1, 4, 1, 1024), (1, 2, 2, 768)])
 def test_prefill_attention(batch, n_q, n_kv, tokens):
     """Causal attention over a whole prompt, element by element against the oracle; several query tiles,
     the diagonal blocks where the mask cuts through a key block, grouped-query sharing, a cache longer
-    than the prompt; atomized == whole and every (sequence, head, query tile) exactly once."""
+    than the prompt; atomized == whole and every (sequence, head, pair of query tiles) exactly once."""
     d, cap = 128, tokens + 64
     qb = inputs.normal_bits((batch * tokens, n_q * d), 51)
     kb = inputs.normal_bits((batch, cap, n_kv, d), 52)
@@ -181,7 +181,7 @@ def test_prefill_attention(batch, n_q, n_kv, tokens):
     q, k, v = dev_bits(qb), dev_bits(kb), dev_bits(vb)
     o = nan_like((batch * tokens, n_q * d), torch.bfloat16)
     total = launch(B.attn_prefill_op(q, k, v, o, batch, n_q, n_kv, d, tokens, cap, scale))
-    assert total == batch * n_q * (tokens // 128)
+    assert total == batch * n_q * (tokens // 256)        # a block computes tile p from the end and tile p from the start
     g = o.cpu().to(torch.float64).numpy()
     assert not np.isnan(g).any()
     # probabilities are rounded to bf16 (2^-9 relative each, averaged over the visible keys) and the
@@ -226,7 +226,7 @@ def test_prefill_attention_refuses_unbuilt_shapes():
     x = torch.zeros((256, 4 * 128), dtype=torch.bfloat16, device="cuda")
     kv = torch.zeros((1, 256, 4, 128), dtype=torch.bfloat16, device="cuda")
     bad = [B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 64, 256, 256, 1.0),        # head width 64
-           B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 128, 200, 256, 1.0),       # not a multiple of 128
+           B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 128, 128, 256, 1.0),       # not a multiple of 256
            B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 128, 512, 256, 1.0),       # longer than the buffers
            B.attn_prefill_op(x, kv, kv, x, 1, 4, 3, 128, 256, 256, 1.0),       # 3 does not divide 4
            B.attn_prefill_op(x, kv, kv, x, 1, 4, 4, 128, 256, 256, 1.0, ldq=256)]
