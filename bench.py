@@ -367,6 +367,8 @@ def main():
     tail = None
     if not args.no_tail_study:
         tw, tn = legs["tail"]
+        tn = min(tn, max(300, int(rate * 10.0)))        # about ten seconds per leg at low request rates
+        tw = min(tw, tn // 5)
         tail = {} if args.no_comparators else comparators(tw, tn, seed=6)
         st0 = B.lithos_tenant_stats(t_be)
         rt = stacked_leg(B, torch, wl, t_hp, t_be, inputs.poisson_arrivals(rate, tw + tn, seed=6), tw)
