@@ -73,6 +73,11 @@ def split_arrivals(arrivals, warm):
     return arrivals[:warm], arrivals[warm:] - base
 
 
+def note(msg):
+    """Progress on stderr (stdout carries the one JSON line): a long input build or leg stays visibly alive."""
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
 def nearest_rank(x, q):
     import numpy as np
     s = np.sort(np.asarray(x))
@@ -155,8 +160,13 @@ def wl_cfg5(args, B, inputs, torch):
     from paper_2504_15465_amd.models import DecoderChain
     b, n_layers = args.batch, args.layers
     H, n_q, n_kv, F, pos = 4096, 32, 8, 14336, 2048
-    layers = inputs.decoder_params(n_layers, H, n_q, n_kv, F, seed=20)
+    layers = []
+    for i0 in range(0, n_layers, 4):                 # same draws as one call (seeds are per layer); 4 layers = 1.7 GB
+        note("drawing decoder weights, layers %d-%d of %d" % (i0, min(n_layers, i0 + 4) - 1, n_layers))
+        layers += inputs.decoder_params(min(n_layers, i0 + 4) - i0, H, n_q, n_kv, F, seed=20, first=i0)
+    note("drawing the key/value cache")
     ks, vs = inputs.decoder_kv_cache(n_layers, b, pos, n_kv, H // n_q, seed=21)
+    note("copying weights and cache to the device")
     chain = DecoderChain(layers, ks, vs, b, n_q, n_kv, pos)
     x = inputs.decoder_hidden(b, H, seed=22)
     chain.set_input(x)
@@ -337,6 +347,7 @@ def main():
         atoms; every leg draws `warm + timed` arrivals of the same process."""
         arr = inputs.poisson_arrivals(rate, warm + timed, seed=seed)
         out = {}
+        note("comparator legs: %d + %d requests at %.0f/s each" % (warm, timed, rate))
         ctx, parts, t_hp, t_be = make_world(B, None, masks=False)
         r = stacked_leg(B, torch, wl, t_hp, None, arr, warm)
         out["hp_alone_full_gpu"] = {k: v for k, v in summarise(r).items() if k != "be_tflops"}
@@ -347,6 +358,7 @@ def main():
         out["unpartitioned_coexecution"] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr, warm))
         drop_world(B, ctx, parts, [t_hp, t_be])
         for name, steal in (("static_masks", 0), ("masks_stealing", 1)):
+            note("leg " + name)
             ctx, parts, t_hp, t_be = make_world(B, sched_cfg(steal, 0))
             out[name] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr, warm))
             drop_world(B, ctx, parts, [t_hp, t_be])
@@ -356,6 +368,7 @@ def main():
 
     # ---- main leg: quotas, stealing, atomization: exactly K timed steps after W warm-up ---------------
     arrivals = inputs.poisson_arrivals(rate, W + K, seed=3)
+    note("main leg: %d + %d requests" % (W, K))
     ctx, parts, t_hp, t_be = make_world(B, sched_cfg(1, 1))
     r = stacked_leg(B, torch, wl, t_hp, t_be, arrivals, W)
     s_hp = B.lithos_tenant_stats(t_hp)
@@ -370,7 +383,7 @@ def main():
         tn = min(tn, max(300, int(rate * 10.0)))        # about ten seconds per leg at low request rates
         tw = min(tw, tn // 5)
         tail = {} if args.no_comparators else comparators(tw, tn, seed=6)
-        st0 = B.lithos_tenant_stats(t_be)
+        note("tail study, full scheduler: %d + %d requests" % (tw, tn))
         rt = stacked_leg(B, torch, wl, t_hp, t_be, inputs.poisson_arrivals(rate, tw + tn, seed=6), tw)
         tail["full_scheduler"] = summarise(rt)
         tail["full_scheduler"]["be_revocations"] = int(rt["s1"].revocations - rt["s0"].revocations)
@@ -405,6 +418,7 @@ def main():
     B.lithos_destroy_partition(p_all)
     B.lithos_shutdown(ctx_p)
 
+    note("cpu baseline (oracle)")
     cpu = None if args.no_cpu_baseline else wl["cpu_baseline"]()
 
     ideal = comp.get("hp_alone_full_gpu", {}).get("p99_us")
@@ -596,7 +610,9 @@ def three_tenants(args, B, inputs, torch):
         st = [B.lithos_tenant_stats(t) for t in ts]
         drop_world(B, ctx, parts, ts)
         res = {"be_tflops": iters * be["flop"] / secs * 1e-12, "be_stolen_atoms": int(st[2].stolen_atoms),
-               "hp_stolen_atoms": int(st[0].stolen_atoms + st[1].stolen_atoms)}
+               "hp_stolen_atoms": int(st[0].stolen_atoms + st[1].stolen_atoms),
+               "hp_rightsized_kernels": int(st[0].rightsized_kernels + st[1].rightsized_kernels),
+               "revocations": int(sum(x.revocations for x in st))}
         for name, skip in (("a", W), ("b", max(10, n_b // 20))):
             lat = out[name][skip:]
             res["hp_" + name] = {"p50_us": nearest_rank(lat, 0.5), "p99_us": nearest_rank(lat, 0.99),
@@ -604,12 +620,18 @@ def three_tenants(args, B, inputs, torch):
                                  "slo_attainment_3x": float(np.mean(lat <= 0.3 * slo[name])), "requests": int(len(lat))}
         return res
 
-    def cfg(steal, atomize):
+    def cfg(steal, atomize, slip=0.0):
         return B.Config.default(atom_duration_us=args.atom_us, max_outstanding=args.max_outstanding,
-                                max_outstanding_hp=64, steal=steal, atomize=atomize)
-    ladder = {"unpartitioned_coexecution": leg(None, False), "static_masks": leg(cfg(0, 0), True),
-              "masks_stealing_atoms": leg(cfg(1, 1), True)}
-    full = ladder["masks_stealing_atoms"]
+                                max_outstanding_hp=64, steal=steal, atomize=atomize, rightsize_slip=slip)
+    ladder = {}
+    for name, c, masks in (("unpartitioned_coexecution", None, False), ("static_masks", cfg(0, 0), True),
+                           ("masks_stealing_atoms", cfg(1, 1), True),
+                           # Section 4.5 in the dispatcher, slip 1.1 (the paper's): a kernel borrows only if it can fill
+                           # more CUs than its quota and the scaling model says the wider set pays
+                           ("masks_stealing_atoms_rightsized", cfg(1, 1, 1.1), True)):
+        note("leg " + name)
+        ladder[name] = leg(c, masks)
+    full = ladder["masks_stealing_atoms_rightsized"]
     line = {"metric": "three tenants: SLO attainment of two high-priority tenants and best-effort throughput",
             "value": min(full["hp_a"]["slo_attainment"], full["hp_b"]["slo_attainment"]), "unit": "fraction of requests within SLO = 10 x solo median (worse tenant)",
             "n_gpus": 1, "steps": K, "warmup": W, "higher_is_better": True, "data": "synthetic", "dtype": "bf16",

@@ -20,7 +20,6 @@
 // one fp32 plane per slice, which SUM_SLICES adds in slice order: each block's
 // arithmetic depends only on its logical index.
 #include "gemm_common.hpp"
-#include <cstdlib>
 
 namespace lithos {
 
@@ -129,8 +128,6 @@ int gemm_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     g.tiles_m = plan.grid.y; g.tiles_n = plan.grid.x;
     g.a_plane = op.dim[3]; g.c_plane = op.dim[4];
     g.k_slices = (int)op.dim[5]; g.c_slice = op.dim[6];
-    static const int prefetch = [] { const char* e = getenv("LITHOS_GEMM_PREFETCH"); return e ? atoi(e) : 0; }();
-    g.prefetch = prefetch;
     gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B, op.flags & LITHOS_F_IN_F32,
                             op.flags & LITHOS_F_SPLIT_A, staged_epilogue(op));
     LITHOS_HIP(launch_kernel(fn, dim3(LITHOS_ATOM_LAUNCH_BLOCKS(atom)), dim3(plan.threads), s, g, atom));

@@ -24,7 +24,6 @@ struct GemmArgs {
     int64_t c_plane;     // OUT_SPLIT: elements between the hi and the lo plane of C
     int k_slices;        // > 1: logical block z computes k-tiles [z*KT/S, (z+1)*KT/S) into fp32 plane z of C
     int64_t c_slice;     // elements between the planes of consecutive K slices
-    int prefetch;        // 256-tile direct-to-LDS kernel: k-tiles ahead that are touched to pull them into L2 (0: off)
 };
 
 // K slices (the logical grid's z axis): slice z of S owns the k-tiles [z*KT/S, (z+1)*KT/S),

@@ -92,28 +92,6 @@ void gemm_lds256_kernel(GemmArgs g, AtomArgs atom)
 
     int kt0, KT;                                    // this block's k-tiles are [kt0, KT)
     slice_ktiles(g, blk.z, g.K / BK, kt0, KT);
-    // L2 warm-up of a later k-tile: every thread touches one 128-byte line of the tile's 64 KB (256 rows
-    // x 128 bytes of a k-contiguous operand, 64 k-rows x 512 bytes of a k-strided one); the value is
-    // never used, and the only wait on vector memory in the loop is the vmcnt(0) in front of the barrier
-    const uint16_t* pf_base;
-    int64_t pf_kstep;
-    {
-        const bool isA = tid < 256;
-        const int t = tid & 255;
-        if (isA) {
-            if constexpr (KSA) { pf_base = g.A + (int64_t)(t >> 2) * g.lda + min(m0 + (t & 3) * 64, g.M - 8); pf_kstep = g.lda; }
-            else { pf_base = g.A + (int64_t)min(m0 + t, g.M - 1) * g.lda; pf_kstep = 1; }
-        } else {
-            if constexpr (KSB) { pf_base = g.B + (int64_t)(t >> 2) * g.ldb + min(n0 + (t & 3) * 64, g.N - 8); pf_kstep = g.ldb; }
-            else { pf_base = g.B + (int64_t)min(n0 + t, g.N - 1) * g.ldb; pf_kstep = 1; }
-        }
-    }
-    // the loads land in ONE register that stays reserved until after the loop's last vmcnt(0): a
-    // register that the compiler believed free would be overwritten whenever a late load returns
-    uint32_t pf_sink = 0;
-    auto touch = [&](int kt) {
-        asm volatile("global_load_dword %0, %1, off" : "+v"(pf_sink) : "v"(pf_base + (int64_t)kt * BK * pf_kstep) : "memory");
-    };
     if (g.k_slices > 1) g.C = reinterpret_cast<float*>(g.C) + (int64_t)blk.z * g.c_slice;
     // Operand fragments: set 0 and set 1 alternate between the four 16-wide k-steps of a tile.
     bf16x8 af[2][MI], bfr[2][NI];
@@ -156,7 +134,6 @@ void gemm_lds256_kernel(GemmArgs g, AtomArgs atom)
     auto tile_step = [&](const uint16_t* Ac, const uint16_t* Bc, uint16_t* An, uint16_t* Bn, int kt) {
         const bool more = kt + 1 < KT;
         if (more) fetch(An, Bn, (kt + 1) * BK);
-        if (g.prefetch > 0 && kt + g.prefetch < KT) touch(kt + g.prefetch);
         __builtin_amdgcn_sched_barrier(0);
         mfmas(af[0], bfr[0], 0, 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -193,7 +170,6 @@ void gemm_lds256_kernel(GemmArgs g, AtomArgs atom)
         tile_step(A0, B0, A1, B1, kt);
         if (kt + 1 < KT) tile_step(A1, B1, A0, B0, kt + 1);
     }
-    asm volatile("" : : "v"(pf_sink));              // every tile step ended with vmcnt(0): the register is quiet now
 
     if constexpr (ST) {
         // the four 32 KB buffers hold rows 0-63, 64-127, 128-191, 192-255 of the bf16 tile

@@ -92,10 +92,11 @@ def encoder_hidden(batch, seq=128, hidden=768, seed=11):
     return normal_f32((batch * seq, hidden), seed)
 
 
-def decoder_params(n_layers=32, hidden=4096, n_q=32, n_kv=8, ffn=14336, seed=20, w_std=0.02):
+def decoder_params(n_layers=32, hidden=4096, n_q=32, n_kv=8, ffn=14336, seed=20, w_std=0.02, first=0):
+    """Layers first .. first+n_layers-1 (every layer draws from its own seed, so a model can be built in pieces)."""
     d = hidden // n_q
     layers = []
-    for i in range(n_layers):
+    for i in range(first, first + n_layers):
         s = lambda j: [seed, i, j]
         layers.append(dict(
             rms1=np.ones((hidden,), np.float32), rms2=np.ones((hidden,), np.float32),
