@@ -100,7 +100,8 @@ def run_ops(ctx, ops, part=None, atom_blocks=0):
 class EncoderChain:
     """Post-LayerNorm encoder stack (QKV GEMM, full attention, out-proj + residual,
     LayerNorm, FFN with GELU + residual, LayerNorm) on [batch*seq, hidden] tokens.
-    The residual stream is fp32; GEMM inputs are its bf16 copy."""
+    The residual stream is fp32; GEMM inputs are split-bf16 pairs (hi + lo planes) of it, the
+    packed qkv tensor that attention reads is plain bf16."""
 
     def __init__(self, layers, batch: int, seq: int = 128, heads: int = 12, device="cuda", tile: int = B.TILE_AUTO):
         self.batch, self.seq, self.heads = batch, seq, heads
