@@ -50,6 +50,7 @@ HBM_PEAK_GBS = 8000.0
 TRAFFIC_BYTES = {256: 1.75e9, 128: 3.36e9}
 ALGORITHMIC_BYTES_8192 = 3 * 8192 * 8192 * 2.0      # A and B read once, C written once, bf16
 TAIL_REQUESTS, TAIL_WARMUP = 2000, 100              # fixed-size legs behind "tail_study" (p99 needs samples)
+TAIL_REQUESTS_LONG, TAIL_WARMUP_LONG = 5000, 200    # the two legs whose tails are compared: static masks, full scheduler
 
 
 def plan_legs(steps, warmup, comparator_cap=1000, comparator_warm_cap=100):
@@ -60,7 +61,7 @@ def plan_legs(steps, warmup, comparator_cap=1000, comparator_warm_cap=100):
     every leg at full length.  Every leg has at least one timed request."""
     k, w = max(1, int(steps)), max(0, int(warmup))
     return {"main": (w, k), "comparator": (min(w, comparator_warm_cap), min(k, comparator_cap)),
-            "tail": (TAIL_WARMUP, TAIL_REQUESTS)}
+            "tail": (TAIL_WARMUP, TAIL_REQUESTS), "tail_long": (TAIL_WARMUP_LONG, TAIL_REQUESTS_LONG)}
 
 
 def split_arrivals(arrivals, warm):
@@ -349,10 +350,11 @@ def main():
         return {"p50_us": nearest_rank(lat, 0.5), "p99_us": nearest_rank(lat, 0.99), "requests": int(len(lat)),
                 "be_tflops": r["be_iters"] * wl["be"]["flop"] / r["be_secs"] * 1e-12}
 
-    def comparators(warm, timed, seed):
+    def comparators(warm, timed, seed, static_long=None):
         """(i) high-priority alone on the whole GPU ("ideal"), (ii) best-effort alone, (iii) unpartitioned
         co-execution (two plain queues, no masks, no atoms), (iv) static masks, (v) masks + stealing without
-        atoms; every leg draws `warm + timed` arrivals of the same process."""
+        atoms; every leg draws `warm + timed` arrivals of the same process (the static-mask leg
+        `static_long` = (warm, timed) of them when given)."""
         arr = inputs.poisson_arrivals(rate, warm + timed, seed=seed)
         out = {}
         note("comparator legs: %d + %d requests at %.0f/s each" % (warm, timed, rate))
@@ -368,7 +370,11 @@ def main():
         for name, steal in (("static_masks", 0), ("masks_stealing", 1)):
             note("leg " + name)
             ctx, parts, t_hp, t_be = make_world(B, sched_cfg(steal, 0))
-            out[name] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr, warm))
+            if name == "static_masks" and static_long:
+                arr_l = inputs.poisson_arrivals(rate, static_long[0] + static_long[1], seed=seed)
+                out[name] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr_l, static_long[0]))
+            else:
+                out[name] = summarise(stacked_leg(B, torch, wl, t_hp, t_be, arr, warm))
             drop_world(B, ctx, parts, [t_hp, t_be])
         return out
 
@@ -390,13 +396,17 @@ def main():
         tw, tn = legs["tail"]
         tn = min(tn, max(300, int(rate * 10.0)))        # about ten seconds per leg at low request rates
         tw = min(tw, tn // 5)
-        tail = {} if args.no_comparators else comparators(tw, tn, seed=6)
-        note("tail study, full scheduler: %d + %d requests" % (tw, tn))
-        rt = stacked_leg(B, torch, wl, t_hp, t_be, inputs.poisson_arrivals(rate, tw + tn, seed=6), tw)
+        lw, ln = legs["tail_long"]                      # static masks and the full scheduler: 5000 requests each
+        ln = min(ln, max(300, int(rate * 25.0)))
+        lw = min(lw, ln // 5)
+        tail = {} if args.no_comparators else comparators(tw, tn, seed=6, static_long=(lw, ln))
+        note("tail study, full scheduler: %d + %d requests" % (lw, ln))
+        rt = stacked_leg(B, torch, wl, t_hp, t_be, inputs.poisson_arrivals(rate, lw + ln, seed=6), lw)
         tail["full_scheduler"] = summarise(rt)
         tail["full_scheduler"]["be_revocations"] = int(rt["s1"].revocations - rt["s0"].revocations)
         tail["full_scheduler"]["be_stolen_atoms"] = int(rt["s1"].stolen_atoms - rt["s0"].stolen_atoms)
         tail["requests_per_leg"], tail["warmup_per_leg"] = tn, tw
+        tail["requests_static_masks_and_full_scheduler"] = ln
         if "static_masks" in tail:
             tail["hp_p99_over_static_masks"] = tail["full_scheduler"]["p99_us"] / tail["static_masks"]["p99_us"]
             tail["be_tflops_over_alone"] = tail["full_scheduler"]["be_tflops"] / tail["be_alone_full_gpu"]["tflops"]

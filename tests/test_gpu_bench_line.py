@@ -34,7 +34,7 @@ def test_driver_command_prints_the_contract_line():
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
     tail = d["tail_study"]
-    assert tail["full_scheduler"]["requests"] == 2000 and tail["static_masks"]["requests"] == 2000
+    assert tail["full_scheduler"]["requests"] == 5000 and tail["static_masks"]["requests"] == 5000
     assert d["scheduler"]["context_totals"]["revocations"] >= d["scheduler"]["be_revocations"]
     # more than one GPU is refused with a message
     r2 = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], cwd=ROOT, capture_output=True, text=True, timeout=60)
