@@ -143,36 +143,48 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs a, Ato
         }
         // accumulator element e of sub-block `sub` is key key_base + 32 sub + 8 (e/4) + 4 half + e%4
         const bool diag = key_base + PF_KB - 1 > q0;        // some key of the block lies after some query
+        // The running maximum is kept in raw score units; the scale (times log2 e) enters as the
+        // factor of one fused multiply-add per score: p = 2^(s c - m c).
+        const float c = a.scale_log2e;
+        if (diag || !live[1]) {                             // uniform over the wavefront
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = key_base + sub * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                    if (!live[sub] || key > qi) s[sub][e] = -INFINITY;
+                }
+        }
         float mloc = -INFINITY;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float x = s[sub][e] * a.scale_log2e;
-                const int key = key_base + sub * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-                if (!live[sub] || (diag && key > qi)) x = -INFINITY;
-                s[sub][e] = x;
-                mloc = fmaxf(mloc, x);
-            }
+            for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, s[sub][e]);
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
         // key 0 is visible to every query and block 0 comes first, so m_new is finite from the start
         const float m_new = fmaxf(m_run, mloc);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        const float mc = m_new * c;
         float lsum = 0.0f;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(s[sub][e] - m_new);
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][e], c, -mc));    // 0 for a masked key
                 s[sub][e] = p;
                 lsum += p;
             }
-        l_run = l_run * alpha + lsum;
+        // Once a query has seen its largest score the maximum stays, and rescaling by exactly 1 would
+        // change nothing: the 64 multiplications are skipped unless some lane's maximum moved.
+        if (__any(m_new != m_run)) {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);      // 1 where the maximum stayed, 0 at the start
+            l_run *= alpha;
 #pragma unroll
-        for (int db = 0; db < PF_D / 32; ++db)
+            for (int db = 0; db < PF_D / 32; ++db)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+            m_run = m_new;
+        }
+        l_run += lsum;
 
         // O^T[d][query] += V^T[d][key] P^T[key][query].  MFMA k-slot j of step (sub, gp) is key
         // 32 sub + 16 gp + 8 (j/4) + 4 half + j%4 = accumulator element 8 gp + j of s[sub]; the V
