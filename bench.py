@@ -106,7 +106,7 @@ def wl_cfg2(args, B, inputs, torch):
     from paper_2504_15465_amd.models import MlpChain
     layers = inputs.mlp_params(6, 4096, seed=1)
     pool_bits = inputs.mlp_requests(pool=64, batch=8, hidden=4096, seed=2)
-    chain = MlpChain(layers, 8, "cuda")
+    chain = MlpChain(layers, 8, "cuda", fused=True)
     pool = [inputs.bits_to_torch(pool_bits[i], "cuda").contiguous() for i in range(64)]
     be = be_gemm_8192(B, inputs, torch, args.be_tile)
 
@@ -503,7 +503,7 @@ def atomization_study(args, B, inputs, torch):
     from paper_2504_15465_amd.models import MlpChain
     layers = inputs.mlp_params(6, 4096, seed=1)
     pool_bits = inputs.mlp_requests(pool=64, batch=8, hidden=4096, seed=2)
-    chain = MlpChain(layers, 8, "cuda")
+    chain = MlpChain(layers, 8, "cuda", fused=True)
     pool = [inputs.bits_to_torch(pool_bits[i], "cuda").contiguous() for i in range(64)]
     hp_requests = [chain.ops(x) for x in pool]
     K, W = max(1, min(args.steps, 1000)), max(0, min(args.warmup, 100))
@@ -581,7 +581,7 @@ def three_tenants(args, B, inputs, torch):
     from paper_2504_15465_amd.models import EncoderChain, MlpChain
     layers = inputs.mlp_params(6, 4096, seed=1)
     pool_bits = inputs.mlp_requests(pool=64, batch=8, hidden=4096, seed=2)
-    mlp = MlpChain(layers, 8, "cuda")
+    mlp = MlpChain(layers, 8, "cuda", fused=True)
     pool = [inputs.bits_to_torch(pool_bits[i], "cuda").contiguous() for i in range(64)]
     req_a = [mlp.ops(x) for x in pool]
     enc = EncoderChain(inputs.encoder_params(12, 768, 3072, seed=10), 1, 128, 12)

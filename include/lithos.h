@@ -69,6 +69,9 @@ enum {
 #define LITHOS_F_IN_F32    (1u << 6)   /* in[0] is fp32 (default bf16) */
 #define LITHOS_F_SPLIT_A   (1u << 7)   /* GEMM: A is a bf16 pair hi + lo (two planes, dim[3] elements apart) */
 #define LITHOS_F_OUT_SPLIT (1u << 8)   /* producer also writes the lo plane: lo = bf16(y - bf16(y)) */
+#define LITHOS_F_NORM_LN   (1u << 9)   /* GEMM: rows of A pass through LAYERNORM (gamma in[4], column sums in[5], eps fparam0) on load */
+#define LITHOS_F_NORM_RMS  (1u << 10)  /* GEMM: rows of A pass through RMSNORM (w in[4], eps fparam0) on load */
+#define LITHOS_F_GLU       (1u << 11)  /* GEMM: B holds N gate rows then N up rows; C = silu(A gate^T) * (A up^T) */
 
 /* GEMM tile selectors for lithos_op_t.tile (0 = library chooses) */
 #define LITHOS_TILE_64     64    /* 64x64 output tile */
@@ -80,8 +83,8 @@ enum {
  * One operator instance.  Unused fields are zero.
  *
  * kind        dim[]                              in[] / out[]                         ld[] / fparam[]
- * GEMM        M,N,K,[a_plane,c_plane,slices,     A,B,bias(f32),residual(f32) / C      lda,ldb,ldc,ldr
- *             slice_plane]
+ * GEMM        M,N,K,[a_plane,c_plane,slices,     A,B,bias(f32),residual(f32),          lda,ldb,ldc,ldr
+ *             slice_plane,colsum_stride]         [gamma(f32),colsums(f32)] / C         fparam0=eps (NORM_*)
  *             slices (dim[5]) > 1 cuts K into that many ranges of whole 64-wide k-tiles (balanced:
  *             range z holds the k-tiles [z*KT/S, (z+1)*KT/S)); the logical grid gets z = slices and
  *             block (x,y,z) writes its fp32 partial tile to plane z of out[0], dim[6] (>= M*ldc)
@@ -89,6 +92,17 @@ enum {
  *             tiles fills the chip that way.  SUM_SLICES on the same queue then adds the planes in
  *             slice order and applies the epilogue, so the result does not depend on how either
  *             launch was cut into atoms.
+ *             NORM_LN / NORM_RMS and GLU fuse a decoder's or an MLP's row kernels into the weight-
+ *             streaming form (TRANS_B, M <= 16; the NORM flags also need IN_F32).  C is the product of
+ *             the rows that LAYERNORM / RMSNORM would have written in fp32, computed as
+ *               r_m * (sum_k (x-c_m) gamma_k B_nk - (mean_m-c_m) * G_n) + H_n       (c_m = x[m,0]),
+ *             RMSNORM: r_m * sum_k x gamma_k B_nk, so it differs from the two-step form by fp32 rounding
+ *             only.  G_n = sum_k gamma_k B_nk and H_n = sum_k beta_k B_nk depend on the weights alone:
+ *             the caller computes them once per weight matrix with this same GEMM (A = the two fp32 rows
+ *             gamma and beta, IN_F32 | OUT_F32, same B) and passes the [2, dim[7]] result as in[5].
+ *             GLU's C[m,n] is what SILU_MUL would have made of the [M,2N] product (B has 2N rows, and so
+ *             have the column sums); it takes no BIAS, GELU, RESIDUAL or OUT_SPLIT.  Each saves a launch
+ *             and the round trip of an intermediate tensor, which is what a request of a few rows is made of.
  * SUM_SLICES  rows,cols,slices,slice_plane       planes(f32),bias(f32),residual(f32) / y   ld0=row stride of the planes,
  *             y = act(sum_z plane_z + bias) + residual; BIAS, GELU, RESIDUAL, OUT_F32 as for GEMM          ld1=of y, ld2=of residual
  * BIAS_ACT    rows,cols                          x,bias(f32) / y

@@ -22,7 +22,7 @@ MAX_SWEEP = 64
 
 OP_GEMM, OP_BIAS_ACT, OP_LAYERNORM, OP_SOFTMAX, OP_ATTN_ENC, OP_ATTN_DEC, OP_RMSNORM, OP_ROPE_KV, OP_SILU_MUL, OP_SPIN, OP_ATTN_MERGE, OP_SUM_SLICES, OP_ATTN_PREFILL = range(1, 14)
 ATTN_MAX_SPLITS = 64
-F_TRANS_A, F_TRANS_B, F_BIAS, F_GELU, F_RESIDUAL, F_OUT_F32, F_IN_F32, F_SPLIT_A, F_OUT_SPLIT = (1 << i for i in range(9))
+F_TRANS_A, F_TRANS_B, F_BIAS, F_GELU, F_RESIDUAL, F_OUT_F32, F_IN_F32, F_SPLIT_A, F_OUT_SPLIT, F_NORM_LN, F_NORM_RMS, F_GLU = (1 << i for i in range(12))
 TILE_AUTO, TILE_SKINNY, TILE_64, TILE_128, TILE_256 = 0, 1, 64, 128, 256
 MASK_STRIPED, MASK_WHOLE_XCD = 0, 1
 CLASS_HP, CLASS_BE = 0, 1
@@ -148,9 +148,13 @@ def make_op(kind, dims=(), flags=0, tile=0, ld=(), fparam=(), inputs=(), outputs
 
 
 def gemm_op(a, b, c, m, n, k, ta=False, tb=False, bias=None, gelu=False, residual=None, tile=0,
-            lda=None, ldb=None, ldc=None, ldr=None, op_id=0, a_split=False, c_split=False, k_slices=0, slice_plane=None) -> Op:
+            lda=None, ldb=None, ldc=None, ldr=None, op_id=0, a_split=False, c_split=False, k_slices=0, slice_plane=None,
+            norm_gamma=None, norm_colsums=None, norm_eps=1e-5, glu=False) -> Op:
     """``a_split``: ``a`` is a [2, M, K] bf16 pair (hi, lo planes); ``c_split``: ``c`` is a [2, M, N] pair;
-    ``k_slices`` > 1: ``c`` is an fp32 [k_slices, M, N] stack of partial planes for ``sum_slices_op``."""
+    ``k_slices`` > 1: ``c`` is an fp32 [k_slices, M, N] stack of partial planes for ``sum_slices_op``;
+    ``norm_gamma``: rows of ``a`` are RMS-normalised on load; with ``norm_colsums`` (the fp32 [2, rows of b]
+    product of the rows gamma and beta with ``b``, made once per weight matrix by this same GEMM) layer-normalised;
+    ``glu``: ``b`` is [2N, K], gate rows then up rows, and ``c`` = silu(gate product) * (up product)."""
     flags = (F_TRANS_A if ta else 0) | (F_TRANS_B if tb else 0) | (F_BIAS if bias is not None else 0)
     flags |= (F_GELU if gelu else 0) | (F_RESIDUAL if residual is not None else 0)
     if isinstance(c, torch.Tensor) and c.dtype == torch.float32:
@@ -161,11 +165,14 @@ def gemm_op(a, b, c, m, n, k, ta=False, tb=False, bias=None, gelu=False, residua
     ldb = ldb if ldb is not None else (k if tb else n)
     ldc = ldc if ldc is not None else n
     ldr = ldr if ldr is not None else n
-    flags |= (F_SPLIT_A if a_split else 0) | (F_OUT_SPLIT if c_split else 0)
+    flags |= (F_SPLIT_A if a_split else 0) | (F_OUT_SPLIT if c_split else 0) | (F_GLU if glu else 0)
+    if norm_gamma is not None:
+        flags |= F_NORM_LN if norm_colsums is not None else F_NORM_RMS
     if k_slices > 1 and slice_plane is None:
         slice_plane = m * ldc
-    return make_op(OP_GEMM, (m, n, k, m * lda if a_split else 0, m * ldc if c_split else 0, k_slices, slice_plane or 0), flags, tile,
-                   (lda, ldb, ldc, ldr), (), (a, b, bias, residual), (c,), op_id)
+    cs_stride = norm_colsums.shape[-1] if isinstance(norm_colsums, torch.Tensor) else 0
+    return make_op(OP_GEMM, (m, n, k, m * lda if a_split else 0, m * ldc if c_split else 0, k_slices, slice_plane or 0, cs_stride), flags, tile,
+                   (lda, ldb, ldc, ldr), (norm_eps if norm_gamma is not None else 0.0,), (a, b, bias, residual, norm_gamma, norm_colsums), (c,), op_id)
 
 
 def sum_slices_op(planes, y, rows, cols, slices, bias=None, gelu=False, residual=None, slice_plane=None,

@@ -36,14 +36,16 @@ static bool staged_epilogue(const lithos_op_t& op)
     return op.ld[2] % 8 == 0 && aligned16(op.out[0]);
 }
 
-static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split, bool st)
+static int norm_of(uint32_t flags) { return (flags & LITHOS_F_NORM_LN) ? 1 : (flags & LITHOS_F_NORM_RMS) ? 2 : 0; }
+
+static gemm_fn variant_fn(int variant, bool ta, bool tb, bool a32, bool split, bool st, int norm)
 {
     switch (variant) {
     case V_LDS256: return st ? gemm_lds256_wide_fn(ta, tb) : gemm_lds256_elem_fn(ta, tb);
     case V_TILE64: return gemm_tile64_fn(ta, tb, split, st);
     case V_TILE128: return gemm_tile128_fn(ta, tb, split, st);
     case V_TILE256: return st ? gemm_tile256_wide_fn(ta, tb) : gemm_tile256_elem_fn(ta, tb);
-    default: return gemm_skinny_fn(variant, a32);
+    default: return gemm_skinny_fn(variant, a32, norm);
     }
 }
 
@@ -80,6 +82,8 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         if (op.dim[6] < M * ldc) return fail(LITHOS_EINVAL, "gemm: slice plane stride (dim[6]) smaller than M*ldc");
         if (slices > (K + 63) / 64) return fail(LITHOS_EINVAL, "gemm: more K slices than 64-wide k-tiles");
     }
+    const int norm = norm_of(op.flags);
+    const bool glu = op.flags & LITHOS_F_GLU, fused = norm || glu;
     int tile = op.tile;
     if (a32 && !(M <= 32 && tb && !ta && (tile == 0 || tile == LITHOS_TILE_SKINNY)))
         return fail(LITHOS_EINVAL, "gemm: fp32 activations (IN_F32) are only taken by the skinny kernel (M <= 32, TRANS_B)");
@@ -98,8 +102,21 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
         if (a32 && (lda % 4)) return fail(LITHOS_EINVAL, "gemm: fp32 activations need lda %% 4 == 0");
         variant = V_SKINNY32;
         if (M <= 16) variant = M <= 4 ? V_SKL4 : M <= 8 ? V_SKL8 : V_SKL16;
-        plan->grid = {(uint32_t)((N + 16 * SKINNY_NB - 1) / (16 * SKINNY_NB)), 1, 1};
+        if (fused && M > 16) return fail(LITHOS_EINVAL, "gemm: NORM_LN, NORM_RMS and GLU need M <= 16");
+        if (norm) {
+            if ((op.flags & LITHOS_F_NORM_LN) && (op.flags & LITHOS_F_NORM_RMS)) return fail(LITHOS_EINVAL, "gemm: NORM_LN and NORM_RMS exclude each other");
+            if (!a32) return fail(LITHOS_EINVAL, "gemm: NORM_LN / NORM_RMS need fp32 activations (IN_F32)");
+            if (!op.in[4] || ((op.flags & LITHOS_F_NORM_LN) && !op.in[5])) return fail(LITHOS_EINVAL, "gemm: NORM_* set but gamma (in[4]) or the column sums (in[5]) are null");
+            if ((op.flags & LITHOS_F_NORM_LN) && op.dim[7] < (glu ? 2 * N : N)) return fail(LITHOS_EINVAL, "gemm: NORM_LN needs the row stride of the column sums (dim[7]) >= the rows of B");
+            if (!(op.fparam[0] >= 0.0f)) return fail(LITHOS_EINVAL, "gemm: NORM_* needs eps (fparam0) >= 0");
+        }
+        if (glu) {
+            if (op.flags & (LITHOS_F_BIAS | LITHOS_F_GELU | LITHOS_F_RESIDUAL | LITHOS_F_OUT_SPLIT)) return fail(LITHOS_EINVAL, "gemm: GLU takes no BIAS, GELU, RESIDUAL or OUT_SPLIT");
+            if (2 * N * ldb * 2 >= (1ll << 32)) return fail(LITHOS_EINVAL, "gemm: the skinny kernel addresses weight rows with 32-bit byte offsets (2N*ldb*2 < 4 GiB with GLU)");
+        }
+        plan->grid = {(uint32_t)(glu ? (N + 15) / 16 : (N + 16 * SKINNY_NB - 1) / (16 * SKINNY_NB)), 1, 1};
     } else if (tile == 64 || tile == 128 || tile == 256) {
+        if (fused) return fail(LITHOS_EINVAL, "gemm: NORM_LN, NORM_RMS and GLU are built into the weight-streaming kernel only (TRANS_B, M <= 16)");
         if (split && tile == 256) return fail(LITHOS_EINVAL, "gemm: SPLIT_A is built for the 64 and 128 tiles only");
         variant = tile == 64 ? V_TILE64 : tile == 128 ? V_TILE128 : V_TILE256;
         if (tile == 256 && K % 64 == 0) variant = V_LDS256;
@@ -110,7 +127,7 @@ int gemm_plan(const lithos_op_t& op, OpPlan* plan)
     plan->total = plan->grid.x * plan->grid.y * plan->grid.z;
     plan->threads = tile_threads(variant);
     plan->variant = variant;
-    plan->wg_per_cu = cached_occupancy((const void*)variant_fn(variant, ta, tb, a32, split, staged_epilogue(op)), tile_threads(variant), 1);
+    plan->wg_per_cu = cached_occupancy((const void*)variant_fn(variant, ta, tb, a32, split, staged_epilogue(op), norm), tile_threads(variant), 1);
     return LITHOS_OK;
 }
 
@@ -128,8 +145,9 @@ int gemm_launch(const lithos_op_t& op, const OpPlan& plan, const AtomArgs& atom,
     g.tiles_m = plan.grid.y; g.tiles_n = plan.grid.x;
     g.a_plane = op.dim[3]; g.c_plane = op.dim[4];
     g.k_slices = (int)op.dim[5]; g.c_slice = op.dim[6];
+    g.gamma = (const float*)op.in[4]; g.colsum = (const float*)op.in[5]; g.ldcs = op.dim[7]; g.eps = op.fparam[0];
     gemm_fn fn = variant_fn(plan.variant, op.flags & LITHOS_F_TRANS_A, op.flags & LITHOS_F_TRANS_B, op.flags & LITHOS_F_IN_F32,
-                            op.flags & LITHOS_F_SPLIT_A, staged_epilogue(op));
+                            op.flags & LITHOS_F_SPLIT_A, staged_epilogue(op), norm_of(op.flags));
     LITHOS_HIP(launch_kernel(fn, dim3(LITHOS_ATOM_LAUNCH_BLOCKS(atom)), dim3(plan.threads), s, g, atom));
     return LITHOS_OK;
 }

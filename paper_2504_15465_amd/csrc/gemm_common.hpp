@@ -24,6 +24,10 @@ struct GemmArgs {
     int64_t c_plane;     // OUT_SPLIT: elements between the hi and the lo plane of C
     int k_slices;        // > 1: logical block z computes k-tiles [z*KT/S, (z+1)*KT/S) into fp32 plane z of C
     int64_t c_slice;     // elements between the planes of consecutive K slices
+    const float* gamma;  // NORM_LN / NORM_RMS: per-k scale of the normalised rows of A
+    const float* colsum; // NORM_LN: [2, ldcs] = the rows gamma and beta multiplied with op(B)
+    int64_t ldcs;
+    float eps;
 };
 
 // K slices (the logical grid's z axis): slice z of S owns the k-tiles [z*KT/S, (z+1)*KT/S),
@@ -213,7 +217,7 @@ gemm_fn gemm_tile256_wide_fn(bool ta, bool tb);
 gemm_fn gemm_tile256_elem_fn(bool ta, bool tb);
 gemm_fn gemm_lds256_wide_fn(bool ta, bool tb);
 gemm_fn gemm_lds256_elem_fn(bool ta, bool tb);
-gemm_fn gemm_skinny_fn(int variant, bool a32);
+gemm_fn gemm_skinny_fn(int variant, bool a32, int norm);
 
 constexpr int SKINNY_WAVES = 8;     // wavefronts per workgroup of the skinny kernels, each owning one slice of K
 constexpr int SKINNY_NB = 2;        // 16-column blocks per workgroup of the skinny kernels

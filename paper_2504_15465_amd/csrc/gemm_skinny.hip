@@ -176,11 +176,16 @@ void gemm_skinny_kernel(GemmArgs g, AtomArgs atom)
 // next K chunk (coalesced), splits them once and keeps the three bf16 planes in
 // its own piece of LDS, from which the operands are read; rows beyond MR read
 // one shared row of zeros.
-// Weights: a load instruction fetches whole 256-byte pieces of 4 weight rows (lane l:
-// row l/16, 16-byte chunk l%16) rather than the operand layout's 64-byte pieces of 16
-// rows - on a 64-CU partition the short pieces stream at 1.2 TB/s, the long ones at
-// 1.8-3.5 - and a 16-row block changes layout through the wavefront's own LDS piece
-// (write as loaded, read back as MFMA fragments) before it is multiplied.
+// Weights: a load instruction fetches whole 128-byte pieces of 8 weight rows (lane l:
+// row l/8, 16-byte chunk l%8) rather than the operand layout's 64-byte pieces of 16
+// rows - on a 64-CU partition the short pieces stream at 1.2 TB/s, these at up to 3.6 -
+// and a 16-row block changes layout through the wavefront's own LDS piece (write as
+// loaded, read back as MFMA fragments) before it is multiplied.  (256-byte pieces of 4
+// rows, chunks of 128 k, stream no faster and their two register buffers leave no room
+// under the 128 registers that two workgroups per CU allow: 64-wide chunks it is.)
+// On a 64-CU partition a large weight matrix streams at that partition's read ceiling and
+// the vector ALUs are the next limit, so the loop is kept lean: nothing is masked but the
+// activations, and no load sits under a condition.
 __device__ __forceinline__ void wave_lds_sync()
 {
     // LDS operations of one wavefront complete in order; this only stops the compiler
@@ -190,7 +195,25 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int MR, int NB, int CH, bool A32>
+// NORM: 0 = activations as stored; NORM_RMS / NORM_LN = the GEMM of the normalised rows, without a
+// pass over the rows before the first chunk.  A row's statistics scale and shift whole output rows,
+// so they can wait for the epilogue:
+//   RMSNorm    sum_k (x r g)_k W_nk = r * sum_k (x g)_k W_nk,                   r = 1/sqrt(mean x^2 + eps);
+//   LayerNorm  sum_k ((x - mu) r g + b)_k W_nk
+//                = r * (sum_k ((x - c) g)_k W_nk - (mu - c) * sum_k g_k W_nk) + sum_k b_k W_nk
+//              with c = the row's first element (sums of x - c and (x - c)^2 lose nothing to
+//              cancellation when c lies among the data).
+// The loop multiplies by gamma while it splits the activations into planes and keeps sum x^2 (and
+// sum (x - c)) per lane; LayerNorm's two column vectors sum_k g_k W_nk and sum_k b_k W_nk depend on the
+// weights alone and come in as an input (this kernel's own product of the rows gamma and beta).
+constexpr int NORM_LN = 1, NORM_RMS = 2;
+
+template <int NX, int NORM>
+struct RowStats {
+    float s1[NX], s2[NX], c[NX];      // per 16-byte load of a lane: sum (x - c), sum (x - c)^2, the shift (0 for RMSNorm)
+};
+
+template <int MR, int NB, int CH, bool A32, int NORM>
 struct SkinnyChunk {
     static constexpr int KC = CH * 32;              // k per chunk
     static constexpr int EPL = A32 ? 4 : 8;         // activation elements per lane and 16-byte load
@@ -198,36 +221,44 @@ struct SkinnyChunk {
     static_assert(MR * KC % (64 * EPL) == 0, "a chunk of activations must fill whole 64-lane 16-byte loads");
     uint4 wv[CH][NB];
     uint4 xv[NX];
+    float4 gv;              // NORM: gamma of this lane's four k (the same k in every one of its loads), as loaded
+    static_assert((64 * EPL) % KC == 0, "a lane keeps one k offset in every one of its activation loads");
+    static_assert(NORM == 0 || A32, "normalised activations are fp32");
 
     static constexpr int CPRW = CH * 4;             // 16-byte chunks of a weight row per chunk of K
     static constexpr int RPI = 64 / CPRW;           // weight rows per load instruction
 
+    bool xlive;             // this lane's k of the activation loads (the same in each) lie inside the wavefront's slice
+
     // kc0 = first k of the chunk; dead = chunk index beyond the slice.  woff[u][j] = byte offset of
     // the weight row that instruction u of 16-row block j reads for this lane (row u*RPI + lane/CPRW).
+    // Loads are unconditional, their addresses clamped into the operands.  Outside the slice the
+    // ACTIVATIONS are zeroed when they are staged; the weights are used as they come: a clamped
+    // address stays in its weight row, whose other elements enter the same outputs anyway, and
+    // finite values times zero add nothing.  Rows beyond M repeat row M - 1: they only reach output
+    // rows that are never stored.
     __device__ __forceinline__ void load(const GemmArgs& g, const uint32_t (&woff)[CH][NB], int kc0, int kend, bool dead, int lane)
     {
-        const uint4 zero = make_uint4(0, 0, 0, 0);
         const int k = kc0 + (lane % CPRW) * 8;
-        const bool klive = !dead && k < kend;
+        const int kx = kc0 + (lane * EPL) % KC;
+        xlive = !dead && kx < kend;
         const char* wk = reinterpret_cast<const char*>(g.B) + (size_t)min(k, g.K - 8) * 2;
 #pragma unroll
         for (int u = 0; u < CH; ++u)
 #pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                const uint4 v = *reinterpret_cast<const uint4*>(wk + woff[u][j]);
-                wv[u][j] = klive ? v : zero;
-            }
+            for (int j = 0; j < NB; ++j) wv[u][j] = *reinterpret_cast<const uint4*>(wk + woff[u][j]);
 #pragma unroll
         for (int i = 0; i < NX; ++i) {
-            const int f = (i * 64 + lane) * EPL;
-            const int row = f / KC, k = kc0 + f % KC;
-            const bool live = !dead && row < g.M && k < kend;
-            const int64_t at = (int64_t)min(row, g.M - 1) * g.lda + min(k, g.K - EPL);
-            uint4 v;
-            if constexpr (A32) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(g.A) + at);
-            else v = *reinterpret_cast<const uint4*>(g.A + at);
-            xv[i] = live ? v : zero;
+            const int row = (i * 64 + lane) * EPL / KC;
+            const int64_t at = (int64_t)min(row, g.M - 1) * g.lda + min(kx, g.K - EPL);
+            if constexpr (A32) xv[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(g.A) + at);
+            else xv[i] = *reinterpret_cast<const uint4*>(g.A + at);
         }
+        if constexpr (NORM != 0) gv = *reinterpret_cast<const float4*>(g.gamma + min(kx, g.K - 4));
+        // every load of the chunk is issued here, before the other chunk's MFMAs: left alone, the
+        // instruction scheduler sinks the activation loads to their first use, behind the wait for the
+        // weights, which puts an L2 round trip into every chunk
+        if constexpr (NORM != 0) __builtin_amdgcn_sched_barrier(0);
     }
 
     // Loaded layout (instruction u: rows u*RPI + lane/CPRW, chunk lane%CPRW) -> MFMA layout (fragment u:
@@ -251,18 +282,36 @@ struct SkinnyChunk {
     }
 
     // x = hi + mid + lo exactly, each a bf16 value (upper 16 bits kept); planes are PL elements apart
+    // NORM: the activations are multiplied by gamma and their sums kept in `rs`; elements outside the
+    // slice stay out of the sums.
     template <int ROW, int PL>
-    __device__ __forceinline__ void stage(uint16_t* xs, int lane) const
+    __device__ __forceinline__ void stage(uint16_t* xs, int lane, RowStats<NX, NORM>& rs) const
     {
+        float gm[4] = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (NORM != 0) {
+            const float ge[4] = {gv.x, gv.y, gv.z, gv.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) gm[e] = xlive ? ge[e] : 0.0f;
+        }
 #pragma unroll
         for (int i = 0; i < NX; ++i) {
             const int f = (i * 64 + lane) * EPL;
             uint16_t* dst = xs + (f / KC) * ROW + f % KC;
+            const uint4 xm = xlive ? xv[i] : make_uint4(0, 0, 0, 0);
             if constexpr (!A32) {
-                *reinterpret_cast<uint4*>(dst) = xv[i];
+                *reinterpret_cast<uint4*>(dst) = xm;
                 continue;
             }
-            const float x[4] = {__uint_as_float(xv[i].x), __uint_as_float(xv[i].y), __uint_as_float(xv[i].z), __uint_as_float(xv[i].w)};
+            float x[4] = {__uint_as_float(xm.x), __uint_as_float(xm.y), __uint_as_float(xm.z), __uint_as_float(xm.w)};
+            if constexpr (NORM != 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float d = NORM == NORM_RMS ? x[e] : (xlive ? x[e] - rs.c[i] : 0.0f);
+                    if constexpr (NORM == NORM_LN) rs.s1[i] += d;
+                    rs.s2[i] += d * d;
+                    x[e] = d * gm[e];
+                }
+            }
             uint32_t h[4], m[4], l[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -304,7 +353,10 @@ struct SkinnyChunk {
     }
 };
 
-template <int MR, int NB, int CH, bool A32>
+// GLU (a flag, NB = 2): the weight matrix holds N gate rows followed by N up rows; a workgroup owns 16
+// output columns, its first 16-row block takes their gate rows and its second their up rows, and it
+// stores silu(gate) * up.
+template <int MR, int NB, int CH, bool A32, int NORM>
 __global__ __launch_bounds__(SKINNY_WAVES * 64, 4)      // 128 registers: two workgroups per CU
 void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
 {
@@ -317,12 +369,14 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
     constexpr int XBYTES = KW * XW;                                           // 16-row weight block while it changes layout
     constexpr int RBYTES = KW * NB * 64 * 16;
     __shared__ __attribute__((aligned(16))) unsigned char smem[XBYTES > RBYTES ? XBYTES : RBYTES];
+    __shared__ float2 stat_part[NORM ? KW : 1][MR];   // per wavefront and row: sum (x - c), sum (x - c)^2 over its K slice
 
     const uint32_t L = atom_logical_block(atom);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r16 = lane & 15, kg = lane >> 4;
-    const int n0 = (int)L * 16 * NB;
+    const bool glu = NB == 2 && (g.flags & LITHOS_F_GLU);
+    const int n0 = glu ? (int)L * 16 : (int)L * 16 * NB;
     const int kq = ((g.K + 32 * KW - 1) / (32 * KW)) * 32;
     const int kbeg = wave * kq, kend = min(g.K, kbeg + kq);
 
@@ -336,13 +390,15 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
     f32x4 acc[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    typedef SkinnyChunk<MR, NB, CH, A32> Chunk;
+    typedef SkinnyChunk<MR, NB, CH, A32, NORM> Chunk;
     uint32_t woff[CH][NB];
 #pragma unroll
     for (int u = 0; u < CH; ++u)
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-            woff[u][j] = (uint32_t)((int64_t)min(n0 + j * 16 + u * Chunk::RPI + lane / Chunk::CPRW, g.N - 1) * g.ldb * 2);
+        for (int j = 0; j < NB; ++j) {
+            const int r = min(n0 + (glu ? 0 : j * 16) + u * Chunk::RPI + lane / Chunk::CPRW, g.N - 1) + (glu ? j * g.N : 0);
+            woff[u][j] = (uint32_t)((int64_t)r * g.ldb * 2);
+        }
 
     // chunks are walked cyclically from a per-workgroup start so that workgroups, whose weight
     // rows are a power-of-two stride apart, do not address the same memory channels together
@@ -352,10 +408,19 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
 
     Chunk c0, c1;
     // a chunk's weights change layout in the piece of LDS that its activations then occupy
+    RowStats<Chunk::NX, NORM> rs;
+#pragma unroll
+    for (int i = 0; i < Chunk::NX; ++i) {
+        rs.s1[i] = rs.s2[i] = rs.c[i] = 0.0f;
+        if constexpr (NORM == NORM_LN) {
+            const int row = (i * 64 + lane) * 4 / KC;
+            if (row < g.M) rs.c[i] = reinterpret_cast<const float*>(g.A)[(int64_t)row * g.lda];
+        }
+    }
     auto settle = [&](Chunk& c) {
         c.to_fragments(xs, lane);
         zero_rows();
-        c.template stage<ROW, PL>(xs, lane);
+        c.template stage<ROW, PL>(xs, lane, rs);
         wave_lds_sync();
     };
     int kc0;
@@ -375,6 +440,16 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
         settle(c0);
     }
 
+    if constexpr (NORM != 0) {
+        // the lanes that loaded one row (KC / 4 neighbours) add up their sums; slices are added in wave order below
+#pragma unroll
+        for (int i = 0; i < Chunk::NX; ++i) {
+#pragma unroll
+            for (int o = KC / 8; o >= 1; o >>= 1) { rs.s1[i] += __shfl_xor(rs.s1[i], o); rs.s2[i] += __shfl_xor(rs.s2[i], o); }
+            const int row = (i * 64 + lane) * 4 / KC;
+            if (lane % (KC / 4) == 0 && row < MR) stat_part[wave][row] = make_float2(rs.s1[i], rs.s2[i]);
+        }
+    }
     __syncthreads();                                  // the reduction buffer overlays the activations
     float (*red)[NB][64][4] = reinterpret_cast<float (*)[NB][64][4]>(smem);
 #pragma unroll
@@ -382,24 +457,74 @@ void gemm_skinny_lds_kernel(GemmArgs g, AtomArgs atom)
     __syncthreads();
     if (wave == 0) {
         // accumulator element e of a lane is D[n = 4*kg + e][m = r16]; slices are added in wave order
+        float v[NB][4];
 #pragma unroll
         for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float v = red[0][j][lane][e];
+                v[j][e] = red[0][j][lane][e];
 #pragma unroll
-                for (int w = 1; w < KW; ++w) v += red[w][j][lane][e];
-                epilogue_store(g, r16, n0 + j * 16 + 4 * kg + e, v);
+                for (int w = 1; w < KW; ++w) v[j][e] += red[w][j][lane][e];
             }
+        if constexpr (NORM != 0) {
+            // this lane's row statistics, then the scale (and shift) that the loop left out
+            float s1 = 0.0f, s2 = 0.0f;
+            if (r16 < MR)
+                for (int w = 0; w < KW; ++w) { s1 += stat_part[w][r16].x; s2 += stat_part[w][r16].y; }
+            const float inv_k = 1.0f / (float)g.K;
+            if constexpr (NORM == NORM_RMS) {
+                const float rinv = 1.0f / sqrtf(s2 * inv_k + g.eps);
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[j][e] *= rinv;
+            } else {
+                const float dm = s1 * inv_k;                                  // mean - c
+                const float rstd = 1.0f / sqrtf(fmaxf(s2 * inv_k - dm * dm, 0.0f) + g.eps);
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        // g.colsum: row 0 = sum_k gamma_k W_nk, row 1 = sum_k beta_k W_nk (ldcs apart)
+                        const int n = min(n0 + (glu ? 0 : j * 16) + 4 * kg + e, g.N - 1) + (glu ? j * g.N : 0);
+                        v[j][e] = rstd * (v[j][e] - dm * g.colsum[n]) + g.colsum[g.ldcs + n];
+                    }
+            }
+        }
+        if (glu) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float gt = v[0][e], up = v[NB - 1][e];
+                epilogue_store(g, r16, n0 + 4 * kg + e, gt / (1.0f + expf(-gt)) * up);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) epilogue_store(g, r16, n0 + j * 16 + 4 * kg + e, v[j][e]);
+        }
     }
 }
 
-gemm_fn gemm_skinny_fn(int variant, bool a32)
+// Chunks are 64 k wide (a load instruction fetches 128-byte pieces of 8 weight rows): with 128-wide
+// chunks two buffers in flight do not fit the 128 registers that two workgroups per CU leave a lane.
+template <int MR>
+static gemm_fn skinny_lds_fn(bool a32, int norm)
+{
+    // bf16 activations fill whole 16-byte loads from 8 rows on
+    if (!a32) return (gemm_fn)gemm_skinny_lds_kernel<(MR < 8 ? 8 : MR), 2, 2, false, 0>;
+    if (norm == NORM_LN) return (gemm_fn)gemm_skinny_lds_kernel<MR, 2, 2, true, NORM_LN>;
+    if (norm == NORM_RMS) return (gemm_fn)gemm_skinny_lds_kernel<MR, 2, 2, true, NORM_RMS>;
+    return (gemm_fn)gemm_skinny_lds_kernel<MR, 2, 2, true, 0>;
+}
+
+// norm: 0, NORM_LN or NORM_RMS (fp32 activations of at most 16 rows only)
+gemm_fn gemm_skinny_fn(int variant, bool a32, int norm)
 {
     switch (variant) {
-    case V_SKL4: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<4, 2, 4, true> : (gemm_fn)gemm_skinny_lds_kernel<4, 2, 4, false>;
-    case V_SKL8: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<8, 2, 4, true> : (gemm_fn)gemm_skinny_lds_kernel<8, 2, 4, false>;
-    case V_SKL16: return a32 ? (gemm_fn)gemm_skinny_lds_kernel<16, 2, 2, true> : (gemm_fn)gemm_skinny_lds_kernel<16, 2, 2, false>;
+    case V_SKL4: return skinny_lds_fn<4>(a32, norm);
+    case V_SKL8: return skinny_lds_fn<8>(a32, norm);
+    case V_SKL16: return skinny_lds_fn<16>(a32, norm);
     default: return a32 ? (gemm_fn)gemm_skinny_kernel<2, SKINNY_NB, true> : (gemm_fn)gemm_skinny_kernel<2, SKINNY_NB, false>;
     }
 }

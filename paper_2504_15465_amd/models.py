@@ -44,26 +44,55 @@ def _wt(bits: np.ndarray, device) -> torch.Tensor:
     return bits_to_torch(np.ascontiguousarray(bits.T), device).contiguous()
 
 
+def norm_colsums(ctx, gamma: torch.Tensor, beta: torch.Tensor, w: torch.Tensor) -> torch.Tensor:
+    """[2, N] fp32: the rows gamma and beta multiplied with the [N, K] weight matrix ``w`` by the
+    weight-streaming GEMM itself; what a GEMM that layer-normalises its rows on load needs of
+    gamma and beta.  Made once per weight matrix (``ctx`` None: in a context of its own)."""
+    n, k = w.shape
+    gb = torch.stack([gamma, beta]).contiguous()
+    out = torch.zeros((2, n), dtype=torch.float32, device=w.device)
+    torch.cuda.synchronize()
+    own = ctx is None
+    if own:
+        ctx = B.lithos_init(w.device.index or 0, None)
+    try:
+        B.lithos_launch_atomized(ctx, B.gemm_op(gb, w, out, 2, n, k, tb=True), (0, 0, 0), 0, None, None)
+        B.lithos_partition_sync(ctx, None)
+    finally:
+        if own:
+            B.lithos_shutdown(ctx)
+    return out
+
+
 class MlpChain:
     """h <- LayerNorm(GELU(h W + b)), n_layers times, batch rows.
 
     Weights are kept [N,K] so that small batches use the weight-streaming
     GEMM; ``tile`` forces an MFMA tile variant (then weights stay [K,N] and
-    the LayerNorm output feeding the next GEMM is bf16)."""
+    the LayerNorm output feeding the next GEMM is bf16).  With ``fused``
+    (at most 16 rows) a layer's LayerNorm is applied by the
+    next layer's GEMM while it loads its rows, so a request is one launch per
+    layer plus the last LayerNorm instead of two per layer."""
 
-    def __init__(self, layers, batch: int, device="cuda", tile: int = B.TILE_AUTO):
+    def __init__(self, layers, batch: int, device="cuda", tile: int = B.TILE_AUTO, fused: bool = False, ctx=None):
         self.batch = batch
         self.hidden = layers[0]["w"].shape[0]
         self.n_layers = len(layers)
         H, Bn = self.hidden, batch
         self.skinny = tile in (B.TILE_AUTO, B.TILE_SKINNY) and batch <= 32
         self.tile = tile
+        self.fused = bool(fused)
+        if self.fused and not (self.skinny and batch <= 16):
+            raise ValueError("the fused chain is built on the weight-streaming GEMM (at most 16 rows)")
         self.w = [(_wt(L["w"], device) if self.skinny else _dev(L["w"], device)) for L in layers]
         self.b = [_f32(L["b"], device) for L in layers]
         self.gamma = [_f32(L["gamma"], device) for L in layers]
         self.beta = [_f32(L["beta"], device) for L in layers]
         self.x = torch.zeros((Bn, H), dtype=torch.bfloat16, device=device)
         self.act = torch.zeros((Bn, H), dtype=torch.float32, device=device)
+        self.act2 = torch.zeros((Bn, H), dtype=torch.float32, device=device) if self.fused else None
+        # layer i + 1 normalises with layer i's gamma and beta: their products with layer i + 1's weights
+        self.colsums = [norm_colsums(ctx, self.gamma[i], self.beta[i], self.w[i + 1]) for i in range(self.n_layers - 1)] if self.fused else []
         hdt = torch.float32 if self.skinny else torch.bfloat16
         self.h = [torch.zeros((Bn, H), dtype=hdt, device=device) for _ in range(2)]
         self.out = torch.zeros((Bn, H), dtype=torch.float32, device=device)
@@ -73,6 +102,15 @@ class MlpChain:
         H, Bn = self.hidden, self.batch
         src = self.x if x is None else x
         ops = []
+        if self.fused:
+            acts = (self.act, self.act2)
+            for i in range(self.n_layers):
+                norm = dict(norm_gamma=self.gamma[i - 1], norm_colsums=self.colsums[i - 1]) if i else {}
+                ops.append(B.gemm_op(src, self.w[i], acts[i % 2], Bn, H, H, tb=True, bias=self.b[i], gelu=True,
+                                     tile=self.tile, op_id=i, **norm))
+                src = acts[i % 2]
+            ops.append(B.layernorm_op(src, self.gamma[-1], self.beta[-1], self.out, Bn, H, op_id=self.n_layers))
+            return ops
         for i in range(self.n_layers):
             ops.append(B.gemm_op(src, self.w[i], self.act, Bn, H, H, tb=self.skinny, bias=self.b[i], gelu=True,
                                  tile=self.tile, op_id=2 * i))
@@ -155,11 +193,17 @@ class EncoderChain:
 class DecoderChain:
     """One decode step of a pre-norm grouped-query decoder stack against a bf16
     key/value cache.  All GEMMs are the weight-streaming kind (weights [N,K],
-    fp32 activations); the cache slot ``pos`` is rewritten on every step."""
+    fp32 activations); the cache slot ``pos`` is rewritten on every step.  With
+    ``fused`` (the default for at most 16 sequences) the two RMSNorms run inside
+    the GEMMs that consume them and SiLU(gate) * up inside the gate/up GEMM: 7
+    launches per layer instead of 10."""
 
     def __init__(self, layers, kcache_bits, vcache_bits, batch: int, n_q: int, n_kv: int, pos: int, device="cuda",
-                 splits: int = 0):
+                 splits: int = 0, fused: bool = None):
         self.batch, self.n_q, self.n_kv, self.pos = batch, n_q, n_kv, pos
+        self.fused = batch <= 16 if fused is None else bool(fused)
+        if self.fused and batch > 16:
+            raise ValueError("the fused decoder step is built on the weight-streaming GEMM (at most 16 rows)")
         # key ranges per (sequence, key/value head): enough workgroups for a few hundred CU slots
         units = (pos + 1 + 31) // 32
         self.splits = splits if splits > 0 else max(1, min(B.ATTN_MAX_SPLITS, units, -(-256 // (batch * n_kv))))
@@ -197,22 +241,26 @@ class DecoderChain:
         ops = [B.bias_act_op(self.x_in, self.x, Bn, H, None, gelu=False)]      # working copy of the input
         S = self.splits
         for li, W in enumerate(self.w):
+            if self.fused:
+                ops.append(B.gemm_op(self.x, W["w_qkv"], self.qkv, Bn, nqkv, H, tb=True, norm_gamma=W["rms1"]))
+            else:
+                ops += [B.rmsnorm_op(self.x, W["rms1"], self.n, Bn, H),
+                        B.gemm_op(self.n, W["w_qkv"], self.qkv, Bn, nqkv, H, tb=True)]
             ops += [
-                B.rmsnorm_op(self.x, W["rms1"], self.n, Bn, H),
-                B.gemm_op(self.n, W["w_qkv"], self.qkv, Bn, nqkv, H, tb=True),
                 B.rope_kv_op(self.qkv, self.kc[li], self.vc[li], Bn, n_q, n_kv, d, self.pos, self.cap),
                 B.attn_dec_op(self.qkv, self.kc[li], self.vc[li], self.att, Bn, n_q, n_kv, d, self.pos + 1, self.cap,
                               1.0 / math.sqrt(d), ldq=nqkv, splits=S, workspace=self.ws if S > 1 else None),
             ]
             if S > 1:
                 ops.append(B.attn_merge_op(self.ws, self.att, Bn, n_q, n_kv, d, S))
-            ops += [
-                B.gemm_op(self.att, W["w_o"], self.x, Bn, H, n_q * d, tb=True, residual=self.x),
-                B.rmsnorm_op(self.x, W["rms2"], self.n, Bn, H),
-                B.gemm_op(self.n, W["w_gu"], self.gu, Bn, 2 * F, H, tb=True),
-                B.silu_mul_op(self.gu, self.act, Bn, F),
-                B.gemm_op(self.act, W["w_d"], self.x, Bn, H, F, tb=True, residual=self.x),
-            ]
+            ops.append(B.gemm_op(self.att, W["w_o"], self.x, Bn, H, n_q * d, tb=True, residual=self.x))
+            if self.fused:
+                ops.append(B.gemm_op(self.x, W["w_gu"], self.act, Bn, F, H, tb=True, norm_gamma=W["rms2"], glu=True))
+            else:
+                ops += [B.rmsnorm_op(self.x, W["rms2"], self.n, Bn, H),
+                        B.gemm_op(self.n, W["w_gu"], self.gu, Bn, 2 * F, H, tb=True),
+                        B.silu_mul_op(self.gu, self.act, Bn, F)]
+            ops.append(B.gemm_op(self.act, W["w_d"], self.x, Bn, H, F, tb=True, residual=self.x))
         for i, o in enumerate(ops):
             o.op_id = i
         return ops

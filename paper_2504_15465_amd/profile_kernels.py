@@ -68,7 +68,7 @@ def main():
         print("prefill %d tokens on %d CUs: median %.1f us, %.0f TFLOP/s (causal flops)" % (T, args.cus, med, flop / med * 1e-6))
     elif args.what in ("mlp", "skinny"):
         layers = inputs.mlp_params(6, 4096, seed=1)
-        chain = MlpChain(layers, 8)
+        chain = MlpChain(layers, 8, fused=True)
         chain.set_input(inputs.mlp_requests(1, 8, 4096, 2)[0])
         ops = chain.ops()
         if args.what == "skinny":

@@ -147,14 +147,17 @@ def test_encoder_chain_matches_oracle(batch, n_layers):
         B.lithos_destroy_partition(part)
 
 
-@pytest.mark.parametrize("batch,n_layers,pos", [(1, 2, 2048), (16, 1, 2048), (3, 2, 100)])
-def test_decoder_chain_matches_oracle(batch, n_layers, pos):
-    """Config-5 high-priority tenant at its real per-layer shape (hidden 4096, 32/8 heads, FFN 14336)."""
+@pytest.mark.parametrize("batch,n_layers,pos,fused", [(1, 2, 2048, True), (1, 2, 2048, False), (16, 1, 2048, True),
+                                                      (3, 2, 100, True), (3, 2, 100, False), (20, 1, 300, False)])
+def test_decoder_chain_matches_oracle(batch, n_layers, pos, fused):
+    """Config-5 high-priority tenant at its real per-layer shape (hidden 4096, 32/8 heads, FFN 14336).
+    ``fused``: the RMSNorms and SiLU(gate) * up run inside the GEMMs next to them."""
     H, n_q, n_kv, F = 4096, 32, 8, 14336
     layers = inputs.decoder_params(n_layers, H, n_q, n_kv, F, seed=20)
     ks, vs = inputs.decoder_kv_cache(n_layers, batch, pos, n_kv, H // n_q, seed=21)
     x = inputs.decoder_hidden(batch, H, seed=22)
-    chain = DecoderChain(layers, ks, vs, batch, n_q, n_kv, pos)
+    chain = DecoderChain(layers, ks, vs, batch, n_q, n_kv, pos, fused=fused)
+    assert chain.fused == fused
     chain.set_input(x)
     run_ops(ctx(), chain.ops())
     out = chain.out.clone()

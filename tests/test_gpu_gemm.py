@@ -161,6 +161,126 @@ def test_skinny_weight_streaming_gemm(m, n, k):
     assert grid_auto == grid and bits_equal(c, c_auto)
 
 
+def _launch(op, atom_blocks=0):
+    torch.cuda.synchronize()
+    B.lithos_launch_atomized(ctx(), op, (0, 0, 0), atom_blocks, None, None)
+    B.lithos_partition_sync(ctx(), None)
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 6, 7, 8, 9, 14, 16])
+@pytest.mark.parametrize("n,k", [(4096, 4096), (1000, 520)])
+@pytest.mark.parametrize("norm", ["ln", "rms"])
+def test_weight_streaming_gemm_normalises_its_rows_on_load(m, n, k, norm):
+    """GEMM with NORM_LN / NORM_RMS against the oracle's row kernel followed by its GEMM (the row counts
+    on both sides of every kernel variant's limit)."""
+    from paper_2504_15465_amd.models import norm_colsums
+    rng = np.random.default_rng(100 * m + k)
+    _, w_bits = inputs.gemm_operands(m, n, k, seed=m + 3, tb=True, dist="normal")
+    x = (0.4 + 1.3 * rng.standard_normal((m, k))).astype(np.float32)     # a mean well away from zero
+    gamma = (1.0 + 0.2 * rng.standard_normal(k)).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(k)).astype(np.float32)
+    eps = 1e-5
+    xn = O.layernorm(x, gamma, beta, eps) if norm == "ln" else O.rmsnorm(x, gamma, eps)
+    ref = O.gemm(xn, w_bits, tb=True)
+    xd, wd = torch.from_numpy(x).cuda(), dev_bits(w_bits)
+    gd, bd = torch.from_numpy(gamma).cuda(), torch.from_numpy(beta).cuda()
+    c = nan_like((m, n), torch.float32)
+    cs = norm_colsums(ctx(), gd, bd, wd) if norm == "ln" else None
+    if cs is not None:       # the column sums are the oracle's products of gamma and beta with the weights
+        assert rel_fro(cs, O.gemm(np.stack([gamma, beta]).astype(np.float64), w_bits, tb=True)) <= FRO_TOL
+    op = B.gemm_op(xd, wd, c, m, n, k, tb=True, norm_gamma=gd, norm_colsums=cs, norm_eps=eps)
+    grid, _ = B.lithos_op_grid(ctx(), op)
+    assert grid == ((n + 31) // 32, 1, 1)
+    _launch(op)
+    assert not torch.isnan(c).any()
+    assert rel_fro(c, ref) <= FRO_TOL
+    # the row kernel followed by the plain GEMM agrees to fp32 rounding of the statistics
+    xn_d = nan_like((m, k), torch.float32)
+    _launch(B.layernorm_op(xd, gd, bd, xn_d, m, k, eps) if norm == "ln" else B.rmsnorm_op(xd, gd, xn_d, m, k, eps))
+    c2 = nan_like((m, n), torch.float32)
+    _launch(B.gemm_op(xn_d, wd, c2, m, n, k, tb=True))
+    assert rel_fro(c, c2.double().cpu().numpy()) <= 1e-5
+    c_atom = nan_like((m, n), torch.float32)
+    _launch(B.gemm_op(xd, wd, c_atom, m, n, k, tb=True, norm_gamma=gd, norm_colsums=cs, norm_eps=eps), 5)
+    assert bits_equal(c, c_atom)
+
+
+@pytest.mark.parametrize("m", [1, 4, 7, 16])
+@pytest.mark.parametrize("f,k", [(2048, 1024), (1000, 520)])
+@pytest.mark.parametrize("a32,rms", [(True, True), (True, False), (False, False)])
+def test_weight_streaming_gemm_with_gated_epilogue(m, f, k, a32, rms):
+    """GLU: [2F,K] weights (gate rows, then up rows) -> silu(x gate^T) * (x up^T), optionally RMS-normalised x."""
+    rng = np.random.default_rng(7 * m + f)
+    a_bits, w_bits = inputs.gemm_operands(m, 2 * f, k, seed=m + 11, tb=True, dist="normal")
+    gamma = (1.0 + 0.2 * rng.standard_normal(k)).astype(np.float32)
+    if a32:
+        x = (0.5 * rng.standard_normal((m, k))).astype(np.float32)
+        xd = torch.from_numpy(x).cuda()
+        xin = O.rmsnorm(x, gamma, 1e-6) if rms else x.astype(np.float64)
+    else:
+        xd, xin = dev_bits(a_bits), a_bits
+    p = O.gemm(xin, w_bits, tb=True)
+    ref = O.silu_mul(p[:, :f], p[:, f:])
+    wd, gd = dev_bits(w_bits), torch.from_numpy(gamma).cuda()
+    for dt in (torch.float32, torch.bfloat16):
+        c = nan_like((m, f), dt)
+        mk = lambda out: B.gemm_op(xd, wd, out, m, f, k, tb=True, glu=True, norm_gamma=gd if rms else None, norm_eps=1e-6)
+        op = mk(c)
+        grid, _ = B.lithos_op_grid(ctx(), op)
+        assert grid == ((f + 15) // 16, 1, 1)
+        cnt = counters(grid[0])
+        B.lithos_debug_block_counters(ctx(), cnt)
+        try:
+            _launch(op)
+        finally:
+            B.lithos_debug_block_counters(ctx(), None)
+        assert cnt.cpu().tolist() == [1] * grid[0]
+        assert not torch.isnan(c.float()).any()
+        if dt == torch.float32:
+            assert rel_fro(c, ref) <= FRO_TOL
+        else:
+            bf16_close(c, ref, abs_tol=2.0 ** -22 * k)
+        c_atom = nan_like((m, f), dt)
+        _launch(mk(c_atom), 3)
+        assert bits_equal(c, c_atom)
+
+
+def test_fused_forms_refuse_what_they_were_not_built_for():
+    x32 = torch.zeros((32, 64), dtype=torch.float32, device="cuda")
+    x16 = torch.zeros((32, 64), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((128, 64), dtype=torch.bfloat16, device="cuda")
+    g = torch.ones(64, dtype=torch.float32, device="cuda")
+    c = torch.zeros((32, 64), dtype=torch.float32, device="cuda")
+    cases = [
+        B.gemm_op(x32, w, c, 32, 64, 64, tb=True, norm_gamma=g),                 # more than 16 rows
+        B.gemm_op(x16, w, c, 8, 64, 64, tb=True, norm_gamma=g),                  # bf16 activations
+        B.gemm_op(x16, w, c, 8, 64, 64, tb=False, glu=True),                     # not the weight-streaming form
+        B.gemm_op(x16, w, c, 64, 64, 64, tb=True, glu=True, tile=64),            # a tile kernel
+        B.gemm_op(x16, w, c, 8, 64, 64, tb=True, glu=True, bias=g),              # GLU with a bias
+        B.gemm_op(x32, w, c, 8, 64, 64, tb=True, glu=True, residual=c),          # GLU with a residual
+    ]
+    cs = torch.zeros((2, 128), dtype=torch.float32, device="cuda")
+    op = B.gemm_op(x32, w, c, 8, 64, 64, tb=True, norm_gamma=g, norm_colsums=cs)
+    op.flags |= B.F_NORM_RMS                                                     # both kinds at once
+    cases.append(op)
+    op = B.gemm_op(x32, w, c, 8, 64, 64, tb=True, norm_gamma=g, norm_colsums=cs)
+    op.dim[7] = 32                                                               # column sums shorter than B has rows
+    cases.append(op)
+    op = B.gemm_op(x32, w, c, 8, 64, 64, tb=True, norm_gamma=g, norm_colsums=cs)
+    op.inp[5] = None                                                             # LayerNorm without its column sums
+    cases.append(op)
+    op = B.gemm_op(x32, w, c, 8, 64, 64, tb=True, norm_gamma=g)
+    op.inp[4] = None                                                             # flag without gamma
+    cases.append(op)
+    op = B.gemm_op(x32, w, c, 8, 64, 64, tb=True, norm_gamma=g, norm_eps=-1.0)   # negative eps
+    cases.append(op)
+    torch.cuda.synchronize()
+    for op in cases:
+        with pytest.raises(B.LithosError) as e:
+            B.lithos_launch_atomized(ctx(), op)
+        assert e.value.code == B.EINVAL
+
+
 @pytest.mark.parametrize("tb", [True, False])
 def test_full_size_8192_cubed_sampled_rows(tb):
     """The benchmark's best-effort GEMM at full size, 256x256 tiles, in the

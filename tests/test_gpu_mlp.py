@@ -17,11 +17,15 @@ pytestmark = pytest.mark.gpu
 E2E_TOL = 1e-2
 
 
-@pytest.mark.parametrize("hidden,batch,n_layers", [(4096, 8, 6), (512, 5, 3), (1024, 16, 2), (1024, 32, 2)])
-def test_mlp_chain_matches_oracle(hidden, batch, n_layers):
+@pytest.mark.parametrize("hidden,batch,n_layers,fused", [(4096, 8, 6, True), (4096, 8, 6, False), (512, 5, 3, True),
+                                                         (1024, 16, 2, True), (1024, 16, 2, False), (1024, 32, 2, False),
+                                                         (4096, 1, 6, True)])
+def test_mlp_chain_matches_oracle(hidden, batch, n_layers, fused):
+    """``fused``: each LayerNorm runs inside the next layer's GEMM (one launch per layer and a last LayerNorm)."""
     layers = inputs.mlp_params(n_layers, hidden, seed=1)
     reqs = inputs.mlp_requests(pool=2, batch=batch, hidden=hidden, seed=2)
-    chain = MlpChain(layers, batch)
+    chain = MlpChain(layers, batch, fused=fused, ctx=ctx())
+    assert len(chain.ops()) == (n_layers + 1 if fused else 2 * n_layers)
     part = B.lithos_create_partition(ctx(), B.lithos_make_mask(ctx(), 64))
     try:
         for r in range(2):
