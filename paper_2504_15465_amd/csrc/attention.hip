@@ -167,24 +167,23 @@ __global__ __launch_bounds__(256) void attn_enc_kernel(AttnArgs a, AtomArgs atom
 // (sequence, key/value head) are cut into `splits` contiguous ranges of 32-key
 // units, one workgroup each, so that a partition's CUs all stream the cache.
 //
-// Lane layout: the 16 lanes of a DPP row share one key; lane c of the row owns
-// head dimensions 8c..8c+7, so a row reads one 256-byte cache row with 16-byte
-// loads and four rows of a wavefront read four neighbouring tokens.  A score is
-// the lane's partial dot product summed over its row (4 DPP steps, after which
-// all 16 lanes hold the same bits), the value sum needs no exchange at all, and
-// each of the 16 rows of a workgroup keeps its own running softmax.  The 16
-// partial softmaxes are merged in a fixed order, then the splits (attn_merge).
-__device__ __forceinline__ float dpp_row_sum(float x)
-{
-#define LITHOS_DPP_ADD(CTRL) x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false))
-    LITHOS_DPP_ADD(0xB1);    // quad_perm [1,0,3,2]
-    LITHOS_DPP_ADD(0x4E);    // quad_perm [2,3,0,1]
-    LITHOS_DPP_ADD(0x141);   // row_half_mirror: the other quad of the same 8 lanes
-    LITHOS_DPP_ADD(0x140);   // row_mirror: the other 8 lanes of the row
-#undef LITHOS_DPP_ADD
-    return x;
-}
-
+// Loads: the 16 lanes of a DPP row share one key; lane c of the row owns head
+// dimensions 8c..8c+7, so a row reads one 256-byte cache row with 16-byte loads
+// and four rows of a wavefront read four neighbouring tokens.
+// Scores: on MFMA 16x16x32 with the KEYS as the row operand, S[key][head] = sum_d
+// K[key][d] (scale q)[head][d].  A unit's keys pass through the wavefront's own
+// piece of LDS to change from the loaded layout to operand fragments; scale*q is
+// kept in LDS as three bf16 planes hi + mid + lo (exact), three MFMAs per key
+// fragment, so a score is an fp32 sum of exact products as it was on the vector
+// ALUs.  Two 16-key blocks per unit, block b row n = key 8(n/4) + 4b + n%4: a lane
+// (head = lane%16, kg = lane/16) then holds the scores of keys 8kg..8kg+7 of ONE
+// head, and the softmax costs one exp per key and head (a row sum left every lane
+// of a row with the same score and the same exp to compute).
+// Values: on the vector ALUs in the loaded layout (no exchange of values); the
+// probabilities reach them through LDS as p[key][head].
+// Every wavefront keeps one running softmax over its units; its four row groups
+// hold partial value sums.  These 16 partial results per workgroup are merged in a
+// fixed order, then the splits (attn_merge).
 __device__ __forceinline__ void unpack_bf16x8(const uint4& u, float* f)
 {
     f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
@@ -193,37 +192,63 @@ __device__ __forceinline__ void unpack_bf16x8(const uint4& u, float* f)
     f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
 }
 
+__device__ __forceinline__ void dec_wave_lds_sync()
+{
+    // LDS operations of one wavefront complete in order; this only stops the compiler
+    // from moving reads of other lanes' data across the writes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte slot of chunk c of key row r in a wavefront's key tile: the 8 lanes that read one chunk
+// column of rows {0-3, 8-11} + 4b (+16) fall into 8 different slots mod 8
+__device__ __forceinline__ int dec_kslot(int r, int c) { return r * 16 + (c ^ ((r & 3) | ((r >> 1) & 4))); }
+
 // Workspace of a split launch (floats): numerators [batch*n_kv][splits][G][D],
 // then (max, denominator) pairs [batch*n_kv][splits][G][2].
 template <int G, bool Q32, bool O32>
-__global__ __launch_bounds__(256) void attn_dec_kernel(AttnArgs a, AtomArgs atom)
+__global__ __launch_bounds__(256, 3) void attn_dec_kernel(AttnArgs a, AtomArgs atom)      // 168 registers: three workgroups per CU
 {
     constexpr int D = 128, R = 8;                 // R keys per lane and step: 32 keys per wavefront step
+    constexpr int QLD = D + 8;                    // padded rows: the G live rows are read without bank conflicts
+    constexpr int KT_BYTES = 32 * 16 * 16;        // a wavefront's key tile: 32 keys x 16 chunks of 16 bytes
+    constexpr int PO_BYTES = 16 * G * D * 4;
+    // the partial value sums overlay the key tiles, which are dead by then
+    __shared__ __attribute__((aligned(16))) unsigned char big[4 * KT_BYTES > PO_BYTES ? 4 * KT_BYTES : PO_BYTES];
+    __shared__ __attribute__((aligned(16))) uint16_t qpl[3][G + 1][QLD];   // scale*q = hi + mid + lo, and a row of zeros
+    __shared__ __attribute__((aligned(16))) float pbuf[4][32][4];           // per wavefront: p[key][head]
+    __shared__ float cbuf[4][4];                                             // per wavefront: rescale factor per head
     __shared__ float part_m[16][G], part_l[16][G];
-    __shared__ __attribute__((aligned(16))) float part_o[16][G][D];
 
     const uint32_t L = atom_logical_block(atom);
     const int S = a.splits;
     const int sp = L % S, bg = L / S;
     const int b = bg / a.n_kv, g = bg % a.n_kv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 15, rg = lane >> 4;
+    const int c = lane & 15, rg = lane >> 4;      // loads and values: chunk of 8 head dimensions, row group
+    const int r16 = c, kg = rg;                   // MFMA: key row / head, k group
 
-    float qf[G][8];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        const int64_t idx = (int64_t)b * a.ldq + (g * G + h) * D + 8 * c;
-        if constexpr (Q32) {
-            const float4 q0 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.q) + idx);
-            const float4 q1 = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(a.q) + idx + 4);
-            qf[h][0] = q0.x; qf[h][1] = q0.y; qf[h][2] = q0.z; qf[h][3] = q0.w;
-            qf[h][4] = q1.x; qf[h][5] = q1.y; qf[h][6] = q1.z; qf[h][7] = q1.w;
-        } else {
-            unpack_bf16x8(*reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(a.q) + idx), qf[h]);
+    for (int i = tid; i < (G + 1) * D; i += 256) {
+        const int h = i / D, d = i % D;
+        float x = 0.0f;
+        if (h < G) {
+            const int64_t idx = (int64_t)b * a.ldq + (g * G + h) * D + d;
+            if constexpr (Q32) x = reinterpret_cast<const float*>(a.q)[idx];
+            else x = attn_bf16_to_f32(reinterpret_cast<const uint16_t*>(a.q)[idx]);
+            x *= a.scale;
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[h][e] *= a.scale;
+        const uint32_t hi = __float_as_uint(x) & 0xffff0000u;
+        const float r1 = x - __uint_as_float(hi);                         // exact
+        const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(mid);                       // exact, at most 8 bits
+        qpl[0][h][d] = (uint16_t)(hi >> 16);
+        qpl[1][h][d] = (uint16_t)(mid >> 16);
+        qpl[2][h][d] = (uint16_t)(__float_as_uint(r2) >> 16);
     }
+    __syncthreads();
 
     const int64_t tok_stride = (int64_t)a.n_kv * D;
     const uint16_t* kbase = a.k + ((int64_t)b * a.cap * a.n_kv + g) * D + 8 * c;
@@ -232,13 +257,16 @@ __global__ __launch_bounds__(256) void attn_dec_kernel(AttnArgs a, AtomArgs atom
     const int U = (T + 31) / 32;                                   // 32-key units
     const int u0 = (int)((int64_t)sp * U / S), u1 = (int)((int64_t)(sp + 1) * U / S);
 
-    float m[G], l[G], acc[G][8];
+    uint4* kt = reinterpret_cast<uint4*>(big + wave * KT_BYTES);
+    const uint16_t* qrow = &qpl[0][min(r16, G)][8 * kg];
+    constexpr int QPLANE = (G + 1) * QLD;
+
+    float m = -INFINITY, l = 0.0f;                // running softmax of head r16 (the same in its four kg lanes; l: this lane's keys)
+    float acc[G][8];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-        m[h] = -INFINITY; l[h] = 0.0f;
+    for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
-    }
 
     for (int u = u0 + wave; u < u1; u += 4) {
         uint4 kx[R], vx[R];
@@ -249,59 +277,84 @@ __global__ __launch_bounds__(256) void attn_dec_kernel(AttnArgs a, AtomArgs atom
             kx[i] = *reinterpret_cast<const uint4*>(kbase + off);
             vx[i] = *reinterpret_cast<const uint4*>(vbase + off);
         }
-        float sc[R][G];
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            float kf[8];
-            unpack_bf16x8(kx[i], kf);
-            const bool live = 32 * u + 4 * i + rg < T;
+        for (int i = 0; i < R; ++i) kt[dec_kslot(4 * i + rg, c)] = kx[i];
+        dec_wave_lds_sync();
+
+        float s8[8];
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                float d = 0.0f;
+        for (int blk = 0; blk < 2; ++blk) {
+            const int row = 8 * (r16 >> 2) + 4 * blk + (r16 & 3);
+            f32x4 sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) d += kf[e] * qf[h][e];
-                d = dpp_row_sum(d);
-                sc[i][h] = live ? d : -INFINITY;
+            for (int st = 0; st < 4; ++st) {
+                const bf16x8 kf = __builtin_bit_cast(bf16x8, kt[dec_kslot(row, 4 * st + kg)]);
+#pragma unroll
+                for (int p = 2; p >= 0; --p) {
+                    const bf16x8 qf = *reinterpret_cast<const bf16x8*>(qrow + p * QPLANE + 32 * st);
+                    sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf, sc, 0, 0, 0);
+                }
             }
+            // element e: key 8*kg + 4*blk + e of the unit, head r16
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s8[4 * blk + e] = 32 * u + 8 * kg + 4 * blk + e < T ? sc[e] : -INFINITY;
         }
+        float bm = s8[0];
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-            float bm = sc[0][h];
+        for (int j = 1; j < 8; ++j) bm = fmaxf(bm, s8[j]);
+        bm = fmaxf(bm, __shfl_xor(bm, 16));
+        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        const float nm = fmaxf(m, bm);
+        const float ref = nm == -INFINITY ? 0.0f : nm;             // a unit always holds a live key; kept for safety
+        const float corr = expf(m - ref);                          // 0 while m = -inf
+        float ls = 0.0f;
 #pragma unroll
-            for (int i = 1; i < R; ++i) bm = fmaxf(bm, sc[i][h]);
-            const float nm = fmaxf(m[h], bm);
-            const float ref = nm == -INFINITY ? 0.0f : nm;        // a row that has seen no live key yet
-            const float corr = expf(m[h] - ref);                  // 0 while m = -inf
-            float ls = l[h] * corr;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[h][e] *= corr;
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                const float p = expf(sc[i][h] - ref);             // 0 for a dead key
-                ls += p;
-                sc[i][h] = p;
-            }
-            l[h] = ls;
-            m[h] = nm;
+        for (int j = 0; j < 8; ++j) {
+            const float p = expf(s8[j] - ref);                     // 0 for a dead key
+            ls += p;
+            if (r16 < G) pbuf[wave][8 * kg + j][r16] = p;
         }
+        l = l * corr + ls;
+        m = nm;
+        if (lane < G) cbuf[wave][lane] = corr;
+        dec_wave_lds_sync();
+
+        float cr[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) cr[h] = cbuf[wave][h];
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] *= cr[h];
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             float vf[8];
             unpack_bf16x8(vx[i], vf);
+            const float4 p4 = *reinterpret_cast<const float4*>(&pbuf[wave][4 * i + rg][0]);
+            const float ph[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
             for (int h = 0; h < G; ++h)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[h][e] += sc[i][h] * vf[e];
+                for (int e = 0; e < 8; ++e) acc[h][e] += ph[h] * vf[e];
         }
+        dec_wave_lds_sync();                                       // the next unit rewrites the tile and p
     }
 
-    // merge the 16 rows' partial softmaxes (wavefront-major, then row) in that order
+    // merge the 16 partial softmaxes (wavefront-major, then row group) in that order: a wavefront's
+    // four row groups share its running maximum, its denominator is booked on the first of them
+    float lt = l + __shfl_xor(l, 16);
+    lt = lt + __shfl_xor(lt, 32);
+    __syncthreads();                                               // every wavefront is done with its key tile
+    float (*part_o)[G][D] = reinterpret_cast<float (*)[G][D]>(big);
     const int slot = wave * 4 + rg;
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        if (c == 0) { part_m[slot][h] = m[h]; part_l[slot][h] = l[h]; }
         *reinterpret_cast<float4*>(&part_o[slot][h][8 * c]) = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
         *reinterpret_cast<float4*>(&part_o[slot][h][8 * c + 4]) = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
+    }
+    if (lane < G) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { part_m[wave * 4 + q][lane] = m; part_l[wave * 4 + q][lane] = q == 0 ? lt : 0.0f; }
     }
     __syncthreads();
     for (int i = tid; i < G * D; i += 256) {
@@ -311,7 +364,7 @@ __global__ __launch_bounds__(256) void attn_dec_kernel(AttnArgs a, AtomArgs atom
         const float ref = gm == -INFINITY ? 0.0f : gm;            // a split without keys: all partials empty
         float num = 0.0f, den = 0.0f;
         for (int w = 0; w < 16; ++w) {
-            const float f = expf(part_m[w][h] - ref);             // 0 for a row that saw no key
+            const float f = expf(part_m[w][h] - ref);             // 0 for a wavefront that saw no key
             num += part_o[w][h][d] * f;
             den += part_l[w][h] * f;
         }
