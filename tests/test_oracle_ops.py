@@ -344,3 +344,39 @@ def test_split_bf16_pair_properties():
     assert np.all(np.abs(v[nz] - x[nz]) <= 2.0**-17 * np.abs(x[nz]))     # two 8-bit significands
     assert ops.round_bf16x2(np.array([1 + 2.0**-9]))[0] == 1 + 2.0**-9   # exactly representable as a pair
     assert np.array_equal(ops.round_bf16x2(hi), hi)                     # bf16 values split as (v, 0)
+
+
+# ---------------------------------------- fused forms of the GEMM's row kernels ---
+
+def test_normalised_rows_times_weights_is_a_scaled_and_shifted_product():
+    """The identities that let a GEMM normalise its rows without a pass over them first (what the
+    weight-streaming kernel's NORM_LN / NORM_RMS forms compute), checked with the oracle's own
+    operators in fp64: statistics act on whole output rows, and the two column vectors of
+    LayerNorm are the products of gamma and of beta with the weights."""
+    rng = np.random.default_rng(5)
+    m, n, k, eps = 5, 24, 64, 1e-5
+    x = 0.7 + 1.9 * rng.standard_normal((m, k))
+    gamma, beta = 1.0 + 0.3 * rng.standard_normal(k), 0.2 * rng.standard_normal(k)
+    _, w_bits = inputs.gemm_operands(m, n, k, seed=3, tb=True, dist="normal")
+    w = ops.bf16_to_f64(w_bits)                                     # [n, k]
+    # RMSNorm
+    r = 1.0 / np.sqrt((x * x).mean(axis=1) + eps)
+    want = ops.gemm(ops.rmsnorm(x, gamma, eps), w_bits, tb=True)
+    got = r[:, None] * ops.gemm(x * gamma, w_bits, tb=True)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    # LayerNorm, sums shifted by the row's first element
+    c = x[:, :1]
+    dm = (x - c).mean(axis=1)
+    var = ((x - c) ** 2).mean(axis=1) - dm ** 2
+    assert np.allclose(var, x.var(axis=1), rtol=1e-12)
+    rstd = 1.0 / np.sqrt(var + eps)
+    colsums = ops.gemm(np.stack([gamma, beta]), w_bits, tb=True)   # [2, n]
+    assert np.allclose(colsums[0], w @ gamma) and np.allclose(colsums[1], w @ beta)
+    want = ops.gemm(ops.layernorm(x, gamma, beta, eps), w_bits, tb=True)
+    got = rstd[:, None] * (ops.gemm((x - c) * gamma, w_bits, tb=True) - dm[:, None] * colsums[0]) + colsums[1]
+    assert np.allclose(got, want, rtol=1e-11, atol=1e-11)
+    # gated epilogue: the [m, 2f] product halves, gate first
+    f = n // 2
+    p = ops.gemm(x, w_bits, tb=True)
+    g, u = p[:, :f], p[:, f:]
+    assert np.allclose(ops.silu_mul(g, u), g / (1.0 + np.exp(-g)) * u, rtol=1e-13)
