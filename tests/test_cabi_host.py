@@ -343,6 +343,72 @@ def test_policy_core_right_sizes_online_like_the_oracle_model(slip):
     B.lithos_core_destroy(h.c)
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_policy_core_matches_oracle_model_on_random_scenarios(seed):
+    """Seeded random tenants, quotas, kernels, arrival times and scheduler settings (atom length,
+    outstanding limits, stealing, atomization, right-sizing slip): the C policy core and the oracle's
+    model emit the same atoms on the same CU groups at the same times, and keep the same books."""
+    rnd = random.Random(1000 + seed)
+    n_hp = rnd.choice([1, 1, 2])
+    cuts = sorted(rnd.sample(range(1, 32), n_hp))                     # group boundaries of the quotas
+    bounds = [0] + cuts + [32]
+    quotas = [frozenset(range(bounds[i], bounds[i + 1])) for i in range(n_hp + 1)]
+    classes = [True] * n_hp + [False]
+    scfg = dict(atom_duration_us=rnd.choice([30.0, 80.0, 150.0, 300.0]), max_outstanding=rnd.randint(1, 3),
+                max_outstanding_hp=rnd.choice([0, 2, 8]), steal=rnd.random() < 0.8, atomize=rnd.random() < 0.8,
+                rightsize_slip=rnd.choice([0.0, 0.0, 1.1, 1.5]))
+    scenario = []
+    be = n_hp
+    for i in range(rnd.randint(10, 40)):                              # best effort: batches of 1-3 kernels, all queued at once
+        for _ in range(rnd.randint(1, 3)):
+            scenario.append((0.0, "submit", be, rnd.choice([96, 512, 1024, 1500]), rnd.choice(["be", "be", "be_flat", "be_small"])))
+        scenario.append((0.0, "sync", be, 0, ""))
+    horizon = rnd.uniform(5000, 50000)
+    for who in range(n_hp):
+        for t in sorted(rnd.uniform(50, horizon) for _ in range(rnd.randint(5, 40))):
+            for _ in range(rnd.randint(1, 3)):
+                scenario.append((t, "submit", who, rnd.choice([16, 48, 64, 200, 256]), rnd.choice(["hp_a", "hp_b"])))
+            scenario.append((t, "sync", who, 0, ""))
+    scenario.sort(key=lambda e: e[0])                                 # stable: same-time events keep their order
+
+    sim = Simulator(SimConfig(**scfg), _lat)
+    sim_ids = [sim.add_tenant(q, hp=c) for q, c in zip(quotas, classes)]
+    for time, kind, who, total, op in scenario:
+        if kind == "submit":
+            sim.submit_at(time, sim_ids[who], Kernel(op, total, 1))
+        else:
+            sim.sync_at(time, sim_ids[who])
+    sim.run()
+    want = [(a.tenant, a.ordinal, a.lo, a.hi, _bits(a.mask), a.stolen, a.predicted_us, a.t_start, a.t_end) for a in sim.trace]
+
+    cfg = B.Config.default(**{k: (int(v) if isinstance(v, bool) else v) for k, v in scfg.items()})
+    h = CoreHarness(cfg, {}, [(B.CLASS_HP if c else B.CLASS_BE, q) for q, c in zip(quotas, classes)])
+    for time, kind, who, total, op in scenario:
+        if kind == "submit":
+            h.push(time, "submit", (h.ids[who], total, op))
+        else:
+            h.push(time, "sync", h.ids[who])
+    h.run()
+    got = [(sim_ids[h.ids.index(t)],) + tuple(rest) for t, *rest in h.trace]
+    assert len(got) == len(want), (scfg, len(got), len(want))
+    for g, w in zip(got, want):
+        assert g[:6] == w[:6], (scfg, g, w)
+        assert (g[6] is None) == (w[6] is None) and (w[6] is None or abs(g[6] - w[6]) < 1e-9)
+        assert abs(g[7] - w[7]) < 1e-9 and abs(g[8] - w[8]) < 1e-9
+    for who in range(n_hp + 1):
+        st = B.lithos_core_stats(h.c, h.ids[who])
+        book = sim.per_tenant[sim_ids[who]]
+        assert (st.atoms, st.stolen_atoms, st.revocations, st.rightsized_kernels) == \
+            (book["atoms"], book["steals"], book["revocations"], book["rightsized"]), (scfg, who)
+        own = _bits(quotas[who])
+        for g in got:
+            if g[0] == sim_ids[who]:
+                assert g[4] & own == own and (g[5] == (g[4] != own))
+                if not scfg["steal"]:
+                    assert g[4] == own
+    B.lithos_core_destroy(h.c)
+
+
 def test_core_refuses_a_slip_below_one():
     with pytest.raises(B.LithosError) as e:
         B.lithos_core_create(B.Config.default(rightsize_slip=0.5), 32, 8)
