@@ -130,6 +130,49 @@ def test_prelude_form_of_algorithm_1_gives_the_same_bits():
     assert rel_fro(outs[(1, 256)], O.gemm(a_bits, b_bits)) <= 1e-4
 
 
+@pytest.mark.parametrize("xcd_remap,prelude", [(1, 0), (0, 0), (1, 1)])
+def test_random_grids_atom_sizes_and_partitions_run_every_block_once_with_the_same_bits(xcd_remap, prelude):
+    """Seeded random GEMM shapes (ragged), tiles, atom sizes (1 block up to more than the grid, not
+    dividing it) and partition sizes: each logical block exactly once, and the bits of a whole launch on
+    the full device, whatever the remapping inside an atom and whichever form of Algorithm 1 is used."""
+    import random
+    rnd = random.Random(17 + 2 * xcd_remap + prelude)
+    base = B.lithos_init(0, None)
+    c = B.lithos_init(0, B.Config.default(xcd_remap=xcd_remap, prelude=prelude))
+    parts = {n: B.lithos_create_partition(c, B.lithos_make_mask(c, n)) for n in (8, 40, 64, 256)}
+    try:
+        for case in range(10):
+            tile = rnd.choice([64, 64, 128, 256])
+            m, n = rnd.randrange(8, 1400, 8), rnd.randrange(8, 1400, 8)
+            k = rnd.randrange(64, 640, 64) if tile == 256 else rnd.randrange(8, 520, 8)
+            a_bits, b_bits = inputs.gemm_operands(m, n, k, seed=100 + case)
+            a, b = dev_bits(a_bits), dev_bits(b_bits)
+            whole = nan_like((m, n), torch.float32)
+            torch.cuda.synchronize()
+            B.lithos_launch_atomized(base, B.gemm_op(a, b, whole, m, n, k, tile=tile), (0, 0, 0), 0, None, None)
+            B.lithos_partition_sync(base, None)
+            out = nan_like((m, n), torch.float32)
+            op = B.gemm_op(a, b, out, m, n, k, tile=tile)
+            grid, _ = B.lithos_op_grid(c, op)
+            total = grid[0] * grid[1] * grid[2]
+            atom_blocks = rnd.choice([1, 2, 3, 5, 7, 13, max(1, total - 1), total + 5, rnd.randint(1, total)])
+            part = parts[rnd.choice([8, 40, 64, 256])]
+            cnt = counters(total)
+            B.lithos_debug_block_counters(c, cnt)
+            try:
+                B.lithos_launch_atomized(c, op, (0, 0, 0), atom_blocks, part, None)
+                B.lithos_partition_sync(c, part)
+            finally:
+                B.lithos_debug_block_counters(c, None)
+            assert cnt.cpu().tolist() == [1] * total, (case, m, n, k, tile, atom_blocks)
+            assert bits_equal(out, whole), (case, m, n, k, tile, atom_blocks)
+    finally:
+        for p in parts.values():
+            B.lithos_destroy_partition(p)
+        B.lithos_shutdown(c)
+        B.lithos_shutdown(base)
+
+
 def test_ordering_stream_chains_launches_on_different_partitions():
     """Kernels of one chain launched on queues with different CU masks, ordered through a stream of the
     caller's: same bits as the chain on one queue, and the caller's own work on that stream runs after."""
