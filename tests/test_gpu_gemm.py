@@ -245,6 +245,76 @@ def test_weight_streaming_gemm_with_gated_epilogue(m, f, k, a32, rms):
         assert bits_equal(c, c_atom)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_weight_streaming_gemm_random_shapes_and_options(seed):
+    """Seeded random rows (1..16), ragged N and K, fp32 or bf16 activations, bias + GELU, residual, the
+    fused normalisations and the gated epilogue in the combinations the kernel takes: against the oracle's
+    operators composed in fp64, and atomized == whole bit for bit."""
+    import random
+    from paper_2504_15465_amd.models import norm_colsums
+    rnd = random.Random(500 + seed)
+    rng = np.random.default_rng(500 + seed)
+    m = rnd.randint(1, 16)
+    n = rnd.choice([8, 24, 40, 72, 136, 200, 328, 600, 1000])
+    k = rnd.choice([8, 16, 40, 64, 72, 200, 256, 520, 776, 1200])
+    a32 = rnd.random() < 0.7
+    norm = rnd.choice([None, None, "rms", "ln"]) if a32 else None
+    glu = rnd.random() < 0.35
+    use_bias = (not glu) and rnd.random() < 0.5
+    use_gelu = (not glu) and rnd.random() < 0.5
+    use_res = (not glu) and rnd.random() < 0.4
+    out_dt = rnd.choice([torch.float32, torch.bfloat16])
+    rows_b = 2 * n if glu else n
+    a_bits, w_bits = inputs.gemm_operands(m, rows_b, k, seed=seed + 40, tb=True, dist="normal")
+    gamma = (1.0 + 0.2 * rng.standard_normal(k)).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(k)).astype(np.float32)
+    bias = (0.3 * rng.standard_normal(n)).astype(np.float32)
+    res = rng.standard_normal((m, n)).astype(np.float32)
+    if a32:
+        x = (0.3 + 0.8 * rng.standard_normal((m, k))).astype(np.float32)
+        xd = torch.from_numpy(x).cuda()
+        xin = x.astype(np.float64)
+        if norm == "rms":
+            xin = O.rmsnorm(x, gamma, 1e-5)
+        elif norm == "ln":
+            xin = O.layernorm(x, gamma, beta, 1e-5)
+    else:
+        xd, xin = dev_bits(a_bits), a_bits
+    p = O.gemm(xin, w_bits, tb=True)
+    if glu:
+        ref = O.silu_mul(p[:, :n], p[:, n:])
+    else:
+        ref = O.bias_act(p, bias if use_bias else None, gelu=use_gelu) if (use_bias or use_gelu) else p
+        if use_res:
+            ref = ref + res
+    wd, gd, bd = dev_bits(w_bits), torch.from_numpy(gamma).cuda(), torch.from_numpy(beta).cuda()
+    cs = norm_colsums(ctx(), gd, bd, wd) if norm == "ln" else None
+    biasd = torch.from_numpy(bias).cuda() if use_bias else None
+    resd = torch.from_numpy(res).cuda() if use_res else None
+    mk = lambda out: B.gemm_op(xd, wd, out, m, n, k, tb=True, bias=biasd, gelu=use_gelu, residual=resd, glu=glu,
+                               norm_gamma=gd if norm else None, norm_colsums=cs, norm_eps=1e-5)
+    c = nan_like((m, n), out_dt)
+    op = mk(c)
+    grid, _ = B.lithos_op_grid(ctx(), op)
+    cnt = counters(grid[0])
+    B.lithos_debug_block_counters(ctx(), cnt)
+    try:
+        _launch(op)
+    finally:
+        B.lithos_debug_block_counters(ctx(), None)
+    what = dict(m=m, n=n, k=k, a32=a32, norm=norm, glu=glu, bias=use_bias, gelu=use_gelu, res=use_res, out=str(out_dt))
+    assert cnt.cpu().tolist() == [1] * grid[0], what
+    assert not torch.isnan(c.float()).any(), what
+    if out_dt == torch.float32:
+        err = np.abs(c.double().cpu().numpy() - ref)
+        assert rel_fro(c, ref) <= FRO_TOL and err.max() <= 1e-5 * max(1.0, np.abs(ref).max()) + 2.0 ** -22 * k, (what, err.max())
+    else:
+        bf16_close(c, ref, exact_frac=0.97, abs_tol=2.0 ** -22 * k + 1e-6)
+    c_atom = nan_like((m, n), out_dt)
+    _launch(mk(c_atom), rnd.choice([1, 2, 3, 5]))
+    assert bits_equal(c, c_atom), what
+
+
 def test_fused_forms_refuse_what_they_were_not_built_for():
     x32 = torch.zeros((32, 64), dtype=torch.float32, device="cuda")
     x16 = torch.zeros((32, 64), dtype=torch.bfloat16, device="cuda")
