@@ -103,6 +103,30 @@ def test_decode_attention(batch, n_q, n_kv, keys, splits, q32):
     assert bits_equal(o, run(3, 1))
 
 
+@pytest.mark.parametrize("batch,n_q,n_kv,keys,splits", [(2, 8, 2, 700, 3), (1, 4, 4, 130, 1), (3, 4, 2, 2049, 16)])
+def test_decode_attention_with_peaked_scores_and_a_strided_query(batch, n_q, n_kv, keys, splits):
+    """Scores spread over +-40 (a few keys carry the whole softmax and the running maximum moves by
+    tens between units), an all-equal-score head (uniform average of the values), and queries read
+    from a wider row (the packed qkv row of a decoder layer)."""
+    d, cap = 128, keys
+    rng = np.random.default_rng(keys)
+    ldq = (n_q + 2 * n_kv) * d
+    q = (rng.standard_normal((batch, ldq)) * 4.0).astype(np.float32)
+    q[:, :d] = 0.0                                                  # head 0: every score is 0
+    kb = inputs.normal_bits((batch, cap, n_kv, d), 61)
+    vb = inputs.normal_bits((batch, cap, n_kv, d), 62)
+    q64 = q[:, :n_q * d].astype(np.float64).reshape(batch, 1, n_q, d)
+    ref = O.attention(q64, O.bf16_to_f64(kb), O.bf16_to_f64(vb), 1 / math.sqrt(d)).reshape(batch, n_q * d)
+    assert np.allclose(ref[:, :d], O.bf16_to_f64(vb)[:, :, 0, :].mean(axis=1), atol=1e-12)
+    qd, k, v = torch.from_numpy(q).cuda(), dev_bits(kb), dev_bits(vb)
+    ws = nan_like((B.attn_workspace_floats(batch, n_q, d, splits),), torch.float32) if splits > 1 else None
+    o = nan_like((batch, n_q * d), torch.float32)
+    launch(B.attn_dec_op(qd, k, v, o, batch, n_q, n_kv, d, keys, cap, 1 / math.sqrt(d), ldq=ldq, splits=splits, workspace=ws))
+    if splits > 1:
+        launch(B.attn_merge_op(ws, o, batch, n_q, n_kv, d, splits))
+    assert np.abs(o.cpu().numpy().astype(np.float64) - ref).max() <= 2e-5
+
+
 def test_decode_attention_split_needs_workspace():
     x = torch.zeros((4, 4 * 128), dtype=torch.float32, device="cuda")
     kv = torch.zeros((4, 64, 4, 128), dtype=torch.bfloat16, device="cuda")
